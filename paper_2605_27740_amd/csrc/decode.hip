@@ -1,0 +1,328 @@
+// Paged decode attention over a list of logical pages per (sequence, KV head):
+//   Eq. 5 of the paper when the list is the selected top-k set, Eq. 4 when it is every page.
+//
+// Split-K: the page list of a row is cut into chunks; one workgroup (4 waves) handles one chunk for all
+// G query heads of the KV head at once, so every K/V byte is read exactly once per step. Inside a wave
+// each lane reads 16-byte chunks of K and V rows (a wave-wide load covers a contiguous 1 KiB of the
+// page), the q.k dot products are reduced across the D/vec lanes that share a token with DPP row
+// operations, and each group of lanes that shares a token row keeps its own online-softmax state, so
+// the inner loop has no cross-row communication. States are merged (log-sum-exp) across lane groups,
+// then across the 4 waves through LDS, and the chunk's partial (o, m, l) goes to the workspace; a
+// second small kernel merges the chunks of a row and writes the output in the cache dtype.
+// Logits are kept in the log2 domain (q is pre-multiplied by sm_scale * log2 e) so exp is one v_exp_f32.
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace unique {
+namespace {
+
+constexpr int kDecWaves = 4;
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename T, int D, int S, int G>
+__global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
+    CacheView c, const T* __restrict__ q, const int32_t* __restrict__ sel_pages,
+    const int32_t* __restrict__ sel_count, int sel_stride, int pages_per_split, int num_splits, float scale_log2,
+    float* __restrict__ part_o /*[rows][num_splits][G][D]*/, float* __restrict__ part_ml /*[rows][num_splits][G][2]*/) {
+  constexpr int kVec = Elem<T>::kVec;
+  constexpr int kLanesPerTok = D / kVec;
+  constexpr int kTokPerLoad = kWave / kLanesPerTok;
+  constexpr int kLoads = S / kTokPerLoad;                       // wave-wide loads per page (K or V)
+  constexpr int kTileLoads = kLoads < 4 ? kLoads : 4;           // loads handled per pipeline stage
+  constexpr int kTilesPerPage = kLoads / kTileLoads;
+  static_assert(S % kTokPerLoad == 0 && kLoads % kTileLoads == 0, "page size / element type combination");
+
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int row = b * c.Hkv + hkv;
+  const int N = c.seq_lens[b];
+  const int P = min((N + S - 1) / S, c.max_pages_hint);
+  const int cnt = sel_pages ? min(sel_count[row], sel_stride) : P;
+  const int begin = split * pages_per_split;
+  if (begin >= cnt) return;
+  const int end = min(begin + pages_per_split, cnt);
+
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int tr = lane / kLanesPerTok, ch = lane % kLanesPerTok;
+
+  float qv[G][kVec];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    load_vec(q + ((int64_t)b * c.H + hkv * G + g) * D + ch * kVec, qv[g]);
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) qv[g][i] *= scale_log2;
+  }
+
+  float m[G], l[G], acc[G][kVec];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = kNegBig;
+    l[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) acc[g][i] = 0.f;
+  }
+
+  const T* kc = reinterpret_cast<const T*>(c.k_cache);
+  const T* vc = reinterpret_cast<const T*>(c.v_cache);
+  const int64_t lane_off = ch * kVec;
+
+  // entries of this chunk are dealt to the waves round-robin; a wave looks up 64 of them at a time
+  for (int e0 = begin + wave; e0 < end; e0 += kDecWaves * kWave) {
+    int my_phys = 0, my_ntok = 0;
+    {
+      const int e = e0 + lane * kDecWaves;
+      if (e < end) {
+        const int lp = sel_pages ? sel_pages[(int64_t)row * sel_stride + e] : e;
+        if (lp >= 0 && lp < P) {
+          const int ph = c.page_table[(int64_t)b * c.max_pages + lp];
+          if (ph >= 0 && (int64_t)ph < c.num_phys) {
+            my_phys = ph;
+            my_ntok = min(S, N - lp * S);
+          }
+        }
+      }
+    }
+    const int n_ent = min(kWave, (end - e0 + kDecWaves - 1) / kDecWaves);
+    const int n_tiles = n_ent * kTilesPerPage;
+
+    Raw16 kr[kTileLoads], vr[kTileLoads], kn[kTileLoads], vn[kTileLoads];
+    int ntok_cur = 0, ntok_nxt = 0, tbase_cur = 0, tbase_nxt = 0;
+    auto issue = [&](int it, Raw16(&kd)[kTileLoads], Raw16(&vd)[kTileLoads], int& ntok, int& tbase) {
+      const int ent = it / kTilesPerPage;
+      const int phys = __builtin_amdgcn_readlane(my_phys, ent);
+      ntok = __builtin_amdgcn_readlane(my_ntok, ent);
+      tbase = (it % kTilesPerPage) * kTileLoads * kTokPerLoad;
+      const int64_t page_off = ((int64_t)phys * c.Hkv + hkv) * (int64_t)(S * D) + lane_off;
+#pragma unroll
+      for (int j = 0; j < kTileLoads; ++j) {
+        const int tok = tbase + j * kTokPerLoad + tr;
+        if (tok < ntok) {
+          kd[j] = load_raw(kc + page_off + (int64_t)tok * D);
+          vd[j] = load_raw(vc + page_off + (int64_t)tok * D);
+        } else {
+          kd[j] = zero_raw();
+          vd[j] = zero_raw();
+        }
+      }
+    };
+
+    issue(0, kr, vr, ntok_cur, tbase_cur);
+    for (int it = 0; it < n_tiles; ++it) {
+      if (it + 1 < n_tiles) issue(it + 1, kn, vn, ntok_nxt, tbase_nxt);
+
+      // logits of this lane group's tokens for the G heads
+      float s[kTileLoads][G];
+#pragma unroll
+      for (int j = 0; j < kTileLoads; ++j) {
+        float kf[kVec];
+        unpack_raw(kr[j], kf, (const T*)nullptr);
+        const bool valid = (tbase_cur + j * kTokPerLoad + tr) < ntok_cur;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float d = qv[g][0] * kf[0];
+#pragma unroll
+          for (int i = 1; i < kVec; ++i) d = fmaf(qv[g][i], kf[i], d);
+          d = group_allreduce<kLanesPerTok>(d, OpSum());
+          s[j][g] = valid ? d : -INFINITY;
+        }
+      }
+      // online softmax update, one state per lane group
+      float p[kTileLoads][G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mx = s[0][g];
+#pragma unroll
+        for (int j = 1; j < kTileLoads; ++j) mx = fmaxf(mx, s[j][g]);
+        const float mnew = fmaxf(m[g], mx);
+        const float alpha = fast_exp2(m[g] - mnew);
+        m[g] = mnew;
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < kTileLoads; ++j) {
+          p[j][g] = fast_exp2(s[j][g] - mnew);
+          psum += p[j][g];
+        }
+        l[g] = fmaf(l[g], alpha, psum);
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) acc[g][i] *= alpha;
+      }
+#pragma unroll
+      for (int j = 0; j < kTileLoads; ++j) {
+        float vf[kVec];
+        unpack_raw(vr[j], vf, (const T*)nullptr);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int i = 0; i < kVec; ++i) acc[g][i] = fmaf(p[j][g], vf[i], acc[g][i]);
+      }
+
+#pragma unroll
+      for (int j = 0; j < kTileLoads; ++j) { kr[j] = kn[j]; vr[j] = vn[j]; }
+      ntok_cur = ntok_nxt;
+      tbase_cur = tbase_nxt;
+    }
+  }
+
+  // merge the lane groups of the wave (they hold disjoint token subsets)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const float M = cross_group_allreduce<kLanesPerTok>(m[g], OpMax());
+    const float sc = fast_exp2(m[g] - M);
+    m[g] = M;
+    l[g] = cross_group_allreduce<kLanesPerTok>(l[g] * sc, OpSum());
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) acc[g][i] = cross_group_allreduce<kLanesPerTok>(acc[g][i] * sc, OpSum());
+  }
+
+  // merge the waves of the workgroup through LDS
+  __shared__ float sm_acc[kDecWaves][G][D];
+  __shared__ float sm_m[kDecWaves][G], sm_l[kDecWaves][G];
+  if (tr == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int i = 0; i < kVec; ++i) sm_acc[wave][g][ch * kVec + i] = acc[g][i];
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+  }
+  __syncthreads();
+  const int64_t pbase = (int64_t)row * num_splits + split;
+  for (int idx = threadIdx.x; idx < G * D; idx += kDecWaves * kWave) {
+    const int g = idx / D, d = idx % D;
+    float M = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) M = fmaxf(M, sm_m[w][g]);
+    float o = 0.f, L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float sc = fast_exp2(sm_m[w][g] - M);
+      o = fmaf(sm_acc[w][g][d], sc, o);
+      L = fmaf(sm_l[w][g], sc, L);
+    }
+    part_o[(pbase * G + g) * D + d] = o;
+    if (d == 0) {
+      part_ml[(pbase * G + g) * 2 + 0] = M;
+      part_ml[(pbase * G + g) * 2 + 1] = L;
+    }
+  }
+}
+
+// Log-sum-exp merge of the chunk partials of one (sequence, query head); writes out (and lse).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(D) void paged_decode_merge_kernel(CacheView c, const int32_t* __restrict__ sel_count,
+                                                               int sel_stride, bool dense, int pages_per_split,
+                                                               int num_splits, const float* __restrict__ part_o,
+                                                               const float* __restrict__ part_ml, T* __restrict__ out,
+                                                               float* __restrict__ lse_out) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int hkv = h / G, g = h % G;
+  const int row = b * c.Hkv + hkv;
+  const int N = c.seq_lens[b];
+  const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);
+  const int cnt = dense ? P : min(sel_count[row], sel_stride);
+  const int ns = min(num_splits, (cnt + pages_per_split - 1) / pages_per_split);
+  const int64_t base = (int64_t)row * num_splits;
+  float M = kNegBig;
+  for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[((base + s) * G + g) * 2]);
+  float o = 0.f, L = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float sc = fast_exp2(part_ml[((base + s) * G + g) * 2] - M);
+    L = fmaf(part_ml[((base + s) * G + g) * 2 + 1], sc, L);
+    o = fmaf(part_o[((base + s) * G + g) * D + d], sc, o);
+  }
+  const bool any = L > 0.f;
+  store_elem(out + ((int64_t)b * c.H + h) * D + d, any ? o / L : 0.f);
+  if (lse_out && d == 0) lse_out[(int64_t)b * c.H + h] = any ? (M + log2f(L)) * kLn2 : -INFINITY;
+}
+
+template <typename T, int D, int S, int G>
+hipError_t launch_t(const CacheView& c, const void* q, const int32_t* sel, const int32_t* cnt, int sel_stride,
+                    int max_list_len, float sm_scale, void* out, float* lse, float* partials, hipStream_t st) {
+  const int rows = c.B * c.Hkv;
+  const SplitPlan plan = plan_splits(rows, max_list_len);
+  float* part_o = partials;
+  float* part_ml = partials + (size_t)rows * plan.num_splits * G * D;
+  const float scale_log2 = (sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)D)) * kLog2e;
+  paged_decode_partial_kernel<T, D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
+      c, reinterpret_cast<const T*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
+      part_o, part_ml);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  paged_decode_merge_kernel<T, D, G><<<dim3(c.H, c.B), dim3(D), 0, st>>>(
+      c, cnt, sel_stride, sel == nullptr, plan.pages_per_split, plan.num_splits, part_o, part_ml,
+      reinterpret_cast<T*>(out), lse);
+  return hipGetLastError();
+}
+
+template <typename T, int D, int S>
+hipError_t dispatch_g(const CacheView& c, const void* q, const int32_t* sel, const int32_t* cnt, int sel_stride,
+                      int max_list_len, float sm_scale, void* out, float* lse, float* partials, hipStream_t st) {
+  switch (c.H / c.Hkv) {
+    case 1: return launch_t<T, D, S, 1>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    case 2: return launch_t<T, D, S, 2>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    case 4: return launch_t<T, D, S, 4>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    case 8: return launch_t<T, D, S, 8>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <typename T, int D>
+hipError_t dispatch_s(const CacheView& c, const void* q, const int32_t* sel, const int32_t* cnt, int sel_stride,
+                      int max_list_len, float sm_scale, void* out, float* lse, float* partials, hipStream_t st) {
+  switch (c.S) {
+    case 8: return dispatch_g<T, D, 8>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    case 16: return dispatch_g<T, D, 16>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    case 32: return dispatch_g<T, D, 32>(c, q, sel, cnt, sel_stride, max_list_len, sm_scale, out, lse, partials, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool decode_supported(int dtype, int D, int S, int G) {
+  return (dtype == 0 || dtype == 1) && (D == 64 || D == 128) && (S == 8 || S == 16 || S == 32) &&
+         (G == 1 || G == 2 || G == 4 || G == 8);
+}
+
+SplitPlan plan_splits(int rows, int max_list_len) {
+  // aim at ~4 workgroups (16 waves) per CU of a 256-CU device, with at least 2 pages per wave
+  constexpr int kTargetGroups = 1024;
+  if (rows < 1) rows = 1;
+  if (max_list_len < 1) max_list_len = 1;
+  const int wanted = (kTargetGroups + rows - 1) / rows;
+  int pps = (max_list_len + wanted - 1) / wanted;
+  if (pps < 2 * kDecWaves) pps = 2 * kDecWaves;
+  pps = (pps + kDecWaves - 1) / kDecWaves * kDecWaves;
+  SplitPlan p;
+  p.pages_per_split = pps;
+  p.num_splits = (max_list_len + pps - 1) / pps;
+  return p;
+}
+
+size_t decode_partial_floats(const CacheView& c, int max_list_len) {
+  const int rows = c.B * c.Hkv;
+  const SplitPlan plan = plan_splits(rows, max_list_len);
+  return (size_t)rows * plan.num_splits * (size_t)(c.H / c.Hkv) * (size_t)(c.D + 2);
+}
+
+hipError_t launch_decode(const CacheView& c, const void* d_q, const int32_t* d_sel_pages,
+                         const int32_t* d_sel_count, int sel_stride, int max_list_len, float sm_scale,
+                         void* d_out, float* d_lse_out, float* d_partials, hipStream_t stream) {
+  if (c.dtype == 0) {
+    return c.D == 64 ? dispatch_s<float, 64>(c, d_q, d_sel_pages, d_sel_count, sel_stride, max_list_len, sm_scale,
+                                             d_out, d_lse_out, d_partials, stream)
+                     : dispatch_s<float, 128>(c, d_q, d_sel_pages, d_sel_count, sel_stride, max_list_len, sm_scale,
+                                              d_out, d_lse_out, d_partials, stream);
+  }
+  return c.D == 64 ? dispatch_s<bf16_t, 64>(c, d_q, d_sel_pages, d_sel_count, sel_stride, max_list_len, sm_scale,
+                                            d_out, d_lse_out, d_partials, stream)
+                   : dispatch_s<bf16_t, 128>(c, d_q, d_sel_pages, d_sel_count, sel_stride, max_list_len, sm_scale,
+                                             d_out, d_lse_out, d_partials, stream);
+}
+
+}  // namespace unique

@@ -1,0 +1,61 @@
+"""Buffer owner for one decode workload: allocates the caller-side device tensors (statistics cache,
+selection, outputs, workspace) with torch and forwards to the C ABI through ``binding``. No arithmetic
+of the method happens here."""
+from __future__ import annotations
+
+import torch
+
+from . import binding
+from .workloads import Workload
+
+
+class DecodeSession:
+    def __init__(self, wl: Workload, top_k: int | None = None, max_seq_len_hint: int | None = None,
+                 want_scores: bool = True, lib: binding.Library | None = None):
+        assert wl.k_cache.is_cuda, "the workload must live on the GPU"
+        self.lib = lib or binding.load()
+        self.wl = wl
+        self.top_k = int(top_k if top_k is not None else wl.top_k)
+        dev = wl.k_cache.device
+        P = wl.num_phys_pages
+        self.page_mean = torch.full((P, wl.Hkv, wl.D), float("nan"), device=dev, dtype=torch.float32)
+        self.page_std = torch.full((P, wl.Hkv), float("nan"), device=dev, dtype=torch.float32)
+        if max_seq_len_hint is None:
+            max_seq_len_hint = int(wl.seq_lens.max().item()) + int(wl.meta.get("spare_tokens", 0))
+        self.desc = binding.make_desc(q_heads=wl.H, k_cache=wl.k_cache, v_cache=wl.v_cache,
+                                      page_mean=self.page_mean, page_std=self.page_std,
+                                      page_table=wl.page_table, seq_lens=wl.seq_lens,
+                                      max_seq_len_hint=max_seq_len_hint)
+        self.sel_pages = torch.full((wl.B, wl.Hkv, self.top_k), -7, device=dev, dtype=torch.int32)
+        self.sel_count = torch.full((wl.B, wl.Hkv), -7, device=dev, dtype=torch.int32)
+        self.scores = (torch.full((wl.B, wl.Hkv, wl.max_pages), float("nan"), device=dev, dtype=torch.float32)
+                       if want_scores else None)
+        self.out = torch.zeros((wl.B, wl.H, wl.D), device=dev, dtype=wl.dtype)
+        self.lse = torch.zeros((wl.B, wl.H), device=dev, dtype=torch.float32)
+        self.out_dense = torch.zeros_like(self.out)
+        self.lse_dense = torch.zeros_like(self.lse)
+        self.workspace_bytes = self.lib.workspace_bytes(self.desc, self.top_k)
+        self.workspace = torch.empty((max(self.workspace_bytes, 256),), device=dev, dtype=torch.uint8)
+        assert self.workspace.data_ptr() % 256 == 0
+
+    # one method per entry point, same names
+    def update_page_stats(self, tok_begin=None, tok_end=None, max_pages_touched_per_seq: int = 0):
+        self.lib.update_page_stats(self.desc, tok_begin, tok_end, max_pages_touched_per_seq)
+
+    def score_select_topk(self, lam: float | None = None):
+        self.lib.score_select_topk(self.desc, self.wl.q, self.top_k, self.wl.lam if lam is None else lam,
+                                   self.sel_pages, self.sel_count, self.scores, self.workspace)
+
+    def sparse_paged_decode(self, sm_scale: float = 0.0, sel_pages=None, sel_count=None):
+        sel_pages = self.sel_pages if sel_pages is None else sel_pages
+        sel_count = self.sel_count if sel_count is None else sel_count
+        self.lib.sparse_paged_decode(self.desc, self.wl.q, sel_pages, sel_count, int(sel_pages.shape[-1]), sm_scale,
+                                     self.out, self.lse, self.workspace)
+
+    def dense_paged_decode(self, sm_scale: float = 0.0):
+        self.lib.dense_paged_decode(self.desc, self.wl.q, sm_scale, self.out_dense, self.lse_dense, self.workspace)
+
+    def sparse_step(self):
+        """score + select + sparse decode (statistics assumed current)."""
+        self.score_select_topk()
+        self.sparse_paged_decode()

@@ -1,0 +1,113 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the header declares,
+and rejects bad host-visible arguments with the documented status codes before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_27740_amd import binding
+from paper_2605_27740_amd.binding import CacheDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def good_desc(**over):
+    # pointers only need to be non-NULL and aligned for validation; nothing dereferences them on the host
+    d = dict(dtype=1, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, batch=2,
+             max_pages_per_seq=64, max_seq_len_hint=0, num_phys_pages=128, k_cache=0x1000, v_cache=0x2000,
+             page_mean=0x3000, page_std=0x4000, page_table=0x5000, seq_lens=0x6000)
+    d.update(over)
+    return CacheDesc(**d)
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "unique.h")).read()
+    declared = set(re.findall(r"\b(unique_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib.c, name)
+    assert lib.version().startswith("unique-gfx950")
+    assert lib.status_string(0) == "ok" and "unknown" in lib.status_string(99)
+
+
+def test_workspace_bytes(lib):
+    n = lib.workspace_bytes(good_desc(), 16)
+    assert n > 0 and n % 256 == 0
+    # needs dimensions only
+    assert lib.workspace_bytes(good_desc(k_cache=0, v_cache=0, page_mean=0, page_std=0, page_table=0, seq_lens=0), 16) == n
+    # grows with the batch, covers score rows
+    assert lib.workspace_bytes(good_desc(batch=64), 16) > n
+    big = lib.workspace_bytes(good_desc(batch=1, max_pages_per_seq=16384), 256)
+    assert big >= 8 * 16384 * 4
+    out = C.c_size_t(0)
+    assert lib.c.unique_workspace_bytes(C.byref(good_desc()), 0, C.byref(out)) == binding.ERR_INVALID_ARG
+    assert lib.c.unique_workspace_bytes(None, 4, C.byref(out)) == binding.ERR_INVALID_ARG
+    assert lib.c.unique_workspace_bytes(C.byref(good_desc()), 4, None) == binding.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(dtype=2), binding.ERR_INVALID_ARG),
+    (dict(batch=0), binding.ERR_INVALID_ARG),
+    (dict(num_q_heads=30), binding.ERR_INVALID_ARG),          # not a multiple of num_kv_heads
+    (dict(head_dim=96), binding.ERR_UNSUPPORTED),
+    (dict(page_size=12), binding.ERR_UNSUPPORTED),
+    (dict(num_q_heads=24, num_kv_heads=8), binding.ERR_UNSUPPORTED),   # G = 3
+    (dict(num_q_heads=12, num_kv_heads=12), binding.ERR_UNSUPPORTED),  # Hkv = 12
+    (dict(k_cache=0), binding.ERR_INVALID_ARG),
+    (dict(page_table=0), binding.ERR_INVALID_ARG),
+    (dict(k_cache=0x1004), binding.ERR_INVALID_ARG),          # misaligned
+    (dict(max_seq_len_hint=-1), binding.ERR_INVALID_ARG),
+])
+def test_descriptor_validation(lib, over, code):
+    rc = lib.c.unique_dense_paged_decode(C.byref(good_desc(**over)), 0x7000, 0.0, 0x8000, None, 0x10000, 1 << 30, None)
+    assert rc == code
+    assert lib.last_error() != ""
+    rc = lib.c.unique_update_page_stats(C.byref(good_desc(**over)), None, None, 0, None)
+    assert rc == code
+
+
+def test_call_argument_validation(lib):
+    d = good_desc()
+    ws, nws = 0x10000, 1 << 30
+    c = lib.c
+    # stats
+    assert c.unique_update_page_stats(None, None, None, 0, None) == binding.ERR_INVALID_ARG
+    assert c.unique_update_page_stats(C.byref(good_desc(page_mean=0)), None, None, 0, None) == binding.ERR_INVALID_ARG
+    assert c.unique_update_page_stats(C.byref(d), 0x100, None, 1, None) == binding.ERR_INVALID_ARG
+    assert c.unique_update_page_stats(C.byref(d), 0x100, 0x200, -1, None) == binding.ERR_INVALID_ARG
+    # score + select
+    f = c.unique_score_select_topk
+    assert f(C.byref(d), None, 4, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(d), 0x7000, 0, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(d), 0x7000, 4, -1.0, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(d), 0x7000, 4, float("nan"), 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(d), 0x7000, 4, 0.5, None, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, None, nws, None) == binding.ERR_WORKSPACE
+    assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, 16, None) == binding.ERR_WORKSPACE
+    assert "too small" in lib.last_error()
+    assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, ws + 8, nws, None) == binding.ERR_WORKSPACE
+    assert f(C.byref(good_desc(page_std=0)), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    # sparse decode
+    g = c.unique_sparse_paged_decode
+    assert g(C.byref(d), 0x7000, None, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert g(C.byref(d), 0x7000, 0x100, 0x200, 0, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert g(C.byref(d), 0x7000, 0x100, 0x200, 4, float("nan"), 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert g(C.byref(d), 0x7004, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert g(C.byref(d), 0x7000, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, 0, None) == binding.ERR_WORKSPACE
+    assert g(C.byref(good_desc(v_cache=0)), 0x7000, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    # dense decode
+    h = c.unique_dense_paged_decode
+    assert h(C.byref(d), 0x7000, 0.0, None, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert h(C.byref(d), 0x7000, 0.0, 0x8000, None, None, 0, None) == binding.ERR_WORKSPACE
+
+
+def test_binding_raises_with_detail(lib):
+    with pytest.raises(binding.UniqueError) as e:
+        lib.workspace_bytes(good_desc(head_dim=80), 4)
+    assert e.value.code == binding.ERR_UNSUPPORTED and "head_dim=80" in str(e.value)

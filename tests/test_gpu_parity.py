@@ -1,0 +1,229 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the float64 oracle.
+
+Small cases are checked on every row; the benchmark-size configurations are generated on the GPU and
+checked on sampled rows (the oracle computes each sampled row by itself). Tolerances are in tests/harness.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_27740_amd import workloads as W
+from paper_2605_27740_amd.session import DecodeSession
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ the five configurations, reduced where needed
+
+def test_config1_tiny_fp32_all_rows(gpu_lib):
+    say("config1 full size")
+    wl = W.config1().to(DEV)
+    _, rep = Hn.full_check(wl)
+    say(rep)
+    assert rep["exact_sets"] == rep["rows"]
+
+
+def test_config1_lambda_zero_is_mean_only(gpu_lib):
+    wl = W.config1().to(DEV)
+    _, rep = Hn.full_check(wl, lam=0.0)
+    assert rep["exact_sets"] == rep["rows"]
+
+
+def test_config2_llama_32k_all_rows(gpu_lib):
+    say("config2 full size (B=1, 32K)")
+    wl = W.config2().to(DEV)
+    _, rep = Hn.full_check(wl, dense_heads=[(0, 0), (0, 13), (0, 31)])
+    say(rep)
+
+
+def test_config3_reduced_all_rows(gpu_lib):
+    say("config3 reduced: B=3 x 8192 tokens, permuted pool")
+    wl = W.config3(batch=3, context=8192, top_k=64).to(DEV)
+    _, rep = Hn.full_check(wl, dense_heads=[(0, 1), (2, 30)])
+    say(rep)
+
+
+def test_config4_reduced_with_appends(gpu_lib):
+    """Ragged batch; each decode step appends one token per sequence and refreshes only the touched page."""
+    say("config4 reduced: B=6, lengths 300..6000, S=32, 40 appended tokens")
+    wl = W.config4(batch=6, min_context=300, max_context=6000, top_k=8, spare_tokens=64).to(DEV)
+    sess = DecodeSession(wl)
+    sess.update_page_stats()
+    for step in range(40):
+        begin = wl.seq_lens.clone()
+        W.append_tokens(wl, step)
+        sess.update_page_stats(begin, wl.seq_lens.clone(), 1)
+        sess.sparse_step()
+    torch.cuda.synchronize()
+    # the incrementally maintained statistics equal a from-scratch rebuild, and the last step is right
+    _, rep = Hn.full_check(wl, sess=sess, run_stats=False, dense_heads=[(1, 5), (4, 17)])
+    say(rep)
+    inc_mean, inc_std = sess.page_mean.clone(), sess.page_std.clone()
+    sess.update_page_stats()
+    torch.cuda.synchronize()
+    used = torch.zeros(wl.num_phys_pages, dtype=torch.bool, device=DEV)
+    for b in range(wl.B):
+        used[wl.page_table[b, :wl.num_pages(b)].long()] = True
+    assert torch.equal(inc_mean[used], sess.page_mean[used]) and torch.equal(inc_std[used], sess.page_std[used])
+
+
+@pytest.mark.parametrize("top_k", [64, 256, 1024])
+def test_config5_reduced_near_ties(gpu_lib, top_k):
+    say(f"config5 reduced: B=2 x 32768 AR(1) tokens, k={top_k}")
+    wl = W.config5(batch=2, context=32768, top_k=top_k).to(DEV)
+    _, rep = Hn.full_check(wl, dense_heads=[(1, 7)])
+    say(rep)
+
+
+# ------------------------------------------------------------------ shapes and edge cases
+
+@pytest.mark.parametrize("dtype,D,S,H,Hkv", [
+    (torch.bfloat16, 128, 8, 8, 2), (torch.bfloat16, 128, 32, 8, 8), (torch.bfloat16, 64, 8, 16, 2),
+    (torch.bfloat16, 64, 16, 16, 16), (torch.bfloat16, 64, 32, 4, 4), (torch.float32, 128, 8, 8, 4),
+    (torch.float32, 128, 16, 2, 1), (torch.float32, 128, 32, 16, 2), (torch.float32, 64, 8, 8, 8),
+    (torch.float32, 64, 32, 2, 2), (torch.bfloat16, 128, 16, 16, 8),
+])
+def test_shape_matrix(gpu_lib, dtype, D, S, H, Hkv):
+    say(f"shape {dtype} D={D} S={S} H={H} Hkv={Hkv}")
+    lens = [5 * S + 3, 1, S, 37 * S - 1]
+    wl = W.build("shape", 7, dtype=dtype, B=4, H=H, Hkv=Hkv, D=D, S=S, seq_lens=lens, top_k=6,
+                 key_mode="shift", plant_mode="one_percent", permute=True, spare_tokens=S).to(DEV)
+    _, rep = Hn.full_check(wl)
+    say(rep)
+
+
+@pytest.mark.parametrize("top_k", [1, 2, 127, 128, 500])
+def test_top_k_extremes(gpu_lib, top_k):
+    wl = W.config1(top_k=top_k).to(DEV)   # P = 128: k=1, k=P-1, k=P, k>P
+    _, rep = Hn.full_check(wl)
+    assert rep["exact_sets"] == rep["rows"]
+
+
+def test_exact_ties_take_lowest_pages(gpu_lib):
+    """All pages identical -> all scores equal -> pages 0..k-1; duplicated pages tie pairwise."""
+    wl = W.config1(poison=False)
+    wl.k_cache[:] = wl.k_cache[0:1].clone()
+    wl = wl.to(DEV)
+    sess, rep = Hn.full_check(wl)
+    assert sess.sel_pages[0, 0].tolist() == list(range(wl.top_k))
+    wl2 = W.config1(poison=False)
+    wl2.k_cache[1::2] = wl2.k_cache[0::2].clone()  # page 2i+1 duplicates page 2i
+    _, rep2 = Hn.full_check(wl2.to(DEV))
+    assert rep2["exact_sets"] == rep2["rows"]
+
+
+def test_select_all_pages_equals_dense(gpu_lib):
+    wl = W.config3(batch=2, context=4096 + 5, top_k=32).to(DEV)
+    sess = DecodeSession(wl)
+    P = wl.num_pages(0)
+    sel = torch.arange(P, device=DEV, dtype=torch.int32).flip(0).repeat(wl.B, wl.Hkv, 1).contiguous()  # any order
+    cnt = torch.full((wl.B, wl.Hkv), P, device=DEV, dtype=torch.int32)
+    sess.sparse_paged_decode(sel_pages=sel, sel_count=cnt)
+    sess.dense_paged_decode()
+    torch.cuda.synchronize()
+    assert (sess.out.float() - sess.out_dense.float()).abs().max().item() <= 2e-2
+    assert (sess.lse - sess.lse_dense).abs().max().item() <= 1e-4
+
+
+def test_invalid_list_entries_are_skipped(gpu_lib):
+    """Entries that are negative or beyond the sequence are ignored, not dereferenced."""
+    wl = W.config1().to(DEV)
+    sess = DecodeSession(wl)
+    good = torch.tensor([3, 9, 100], device=DEV, dtype=torch.int32)
+    sel = torch.tensor([3, -1, 9, 4096, 100, -5], device=DEV, dtype=torch.int32).repeat(1, wl.Hkv, 1).contiguous()
+    cnt = torch.full((1, wl.Hkv), 6, device=DEV, dtype=torch.int32)
+    sess.sparse_paged_decode(sel_pages=sel, sel_count=cnt)
+    torch.cuda.synchronize()
+    oc, q = Hn.oracle_cache(wl)
+    for h in range(wl.H):
+        Hn.check_attention_head(sess.out, sess.lse, oc, q, 0, h, good.cpu().numpy(), wl.dtype)
+    # an empty list gives a zero row and lse = -inf
+    cnt.zero_()
+    sess.sparse_paged_decode(sel_pages=sel, sel_count=cnt)
+    torch.cuda.synchronize()
+    assert (sess.out == 0).all() and torch.isinf(sess.lse).all() and (sess.lse < 0).all()
+
+
+def test_explicit_sm_scale(gpu_lib):
+    wl = W.config1().to(DEV)
+    sess = DecodeSession(wl)
+    sess.update_page_stats()
+    sess.score_select_topk()
+    sess.sparse_paged_decode(sm_scale=0.05)
+    torch.cuda.synchronize()
+    oc, q = Hn.oracle_cache(wl)
+    T = sess.sel_pages[0, 1, :wl.top_k].cpu().numpy()
+    Hn.check_attention_head(sess.out, sess.lse, oc, q, 0, 5, T, wl.dtype, sm_scale=0.05)
+
+
+def test_range_update_touches_only_its_pages(gpu_lib):
+    wl = W.config3(batch=2, context=1000, top_k=8).to(DEV)
+    sess = DecodeSession(wl)
+    begin = torch.tensor([100, 990], device=DEV, dtype=torch.int32)
+    end = torch.tensor([140, 5000], device=DEV, dtype=torch.int32)   # second range is clamped to seq_len
+    sess.update_page_stats(begin, end, 4)
+    torch.cuda.synchronize()
+    oc, _ = Hn.oracle_cache(wl)
+    touched = {0: range(100 // 16, 139 // 16 + 1), 1: range(990 // 16, 999 // 16 + 1)}
+    for b in range(2):
+        P = wl.num_pages(b)
+        phys = wl.page_table[b, :P].long()
+        finite = torch.isfinite(sess.page_std[phys, 0]).cpu().numpy()
+        assert np.nonzero(finite)[0].tolist() == list(touched[b])
+        Hn.check_stats_row(sess, oc, b, 3, pages=list(touched[b]))
+
+
+def test_results_are_bitwise_reproducible(gpu_lib):
+    wl = W.config3(batch=2, context=8192, top_k=64).to(DEV)
+    outs = []
+    for _ in range(2):
+        sess = DecodeSession(wl)
+        sess.update_page_stats()
+        sess.sparse_step()
+        sess.dense_paged_decode()
+        torch.cuda.synchronize()
+        outs.append((sess.sel_pages.clone(), sess.out.clone(), sess.lse.clone(), sess.out_dense.clone(),
+                     sess.page_mean.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.uint8) if a.dtype == torch.bfloat16 else a,
+                           b.view(torch.uint8) if b.dtype == torch.bfloat16 else b)
+
+
+# ------------------------------------------------------------------ benchmark-size configurations, sampled rows
+
+def _sampled(wl, n_rows, seed):
+    rng = np.random.default_rng(seed)
+    rows = {(int(rng.integers(wl.B)), int(rng.integers(wl.Hkv))) for _ in range(4 * n_rows)}
+    return sorted(rows)[:n_rows]
+
+
+def test_config3_full_size_sampled(gpu_lib):
+    say("config3 full size: B=16 x 131072, k=256 (sampled rows)")
+    wl = W.config3(device=DEV)
+    rows = _sampled(wl, 3, 3)
+    _, rep = Hn.full_check(wl, rows=rows, dense_heads=[(rows[0][0], rows[0][1] * wl.G + 2)])
+    say(rep)
+
+
+def test_config4_full_size_sampled(gpu_lib):
+    say("config4 full size: B=32 ragged 4K..128K, S=32, k=64 (sampled rows)")
+    wl = W.config4(device=DEV)
+    order = torch.argsort(wl.seq_lens).tolist()
+    rows = [(order[0], 0), (order[len(order) // 2], 5), (order[-1], 7)]   # shortest, median, longest
+    _, rep = Hn.full_check(wl, rows=rows, dense_heads=[(order[0], 3)])
+    say(rep)
+
+
+@pytest.mark.parametrize("top_k", [64, 1024])
+def test_config5_full_size_sampled(gpu_lib, top_k):
+    say(f"config5 full size: B=4 x 262144 AR(1), k={top_k} (sampled rows)")
+    wl = W.config5(device=DEV, top_k=top_k)
+    _, rep = Hn.full_check(wl, rows=[(0, 1), (3, 2)], dense_heads=[(3, 9)])
+    say(rep)
