@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the UNIQUE sparse decode step on one MI355X.
+
+One "step" = one pass of the hot path over one batch of synthetic input that is already resident in HBM:
+  unique_update_page_stats on the last token of every sequence (tail-page refresh)
+  -> unique_score_select_topk (Eq. 6 scores + top-k)  -> unique_sparse_paged_decode (Eq. 5).
+unique_dense_paged_decode (Eq. 4) is timed beside it as the in-library comparison point, and the float64
+CPU oracle is timed on a bounded sample of the same workload as a reported baseline.
+
+Prints ONE JSON line (see the keys at the bottom). Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+[--workload c2|c3|c4|c5] [--top-k K] [--no-cpu-baseline] [--copy-calibration BYTES]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--top-k", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="only run a device-to-device copy of this many bytes (counter calibration for rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(wl, sess, sel_count, seq_lens):
+    """Bytes the method itself must move per launch, per kernel (the numerators of achieved GB/s)."""
+    e = 2 if str(wl.dtype).endswith("bfloat16") else 4
+    S, D, G, Hkv, H, B = wl.S, wl.D, wl.G, wl.Hkv, wl.H, wl.B
+    pages = [(int(n) + S - 1) // S for n in seq_lens]
+    tot_pages = sum(pages)
+    out = {}
+    # tail-page stats: the valid keys of the last page of each (b, hkv) read, D+1 floats written
+    tail = [int(n) - (p - 1) * S for n, p in zip(seq_lens, pages)]
+    out["page_stats_kernel"] = sum(t * D * e * Hkv for t in tail) + B * Hkv * (D + 1) * 4
+    # score: mean + std read per (b, hkv, page), one page-table entry per (b, page), one float written
+    out["page_score_kernel"] = tot_pages * Hkv * (D * 4 + 4) + tot_pages * 4 + tot_pages * Hkv * 4 + B * H * D * e
+    # select: the score row read once, k_b + 1 ints written
+    out["topk_select_kernel"] = tot_pages * Hkv * 4 + int(sel_count.sum()) * 4 + B * Hkv * 4
+    # sparse decode: K and V of the selected pages (full pages; at most one per row is partial), list + table
+    # entries, q, and the split-K partials written once
+    k_total = int(sel_count.sum())
+    kv = k_total * S * D * 2 * e
+    out["paged_decode_partial_kernel"] = kv + k_total * 8 + B * H * D * e
+    out["paged_decode_partial_kernel_dense"] = tot_pages * Hkv * S * D * 2 * e + tot_pages * Hkv * 4 + B * H * D * e
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU only (asked for --gpus {args.gpus}); the path has no cross-GPU part.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+
+    if args.copy_calibration:
+        n = args.copy_calibration
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": n, "launches": 5}))
+        return
+
+    from paper_2605_27740_amd import workloads as W
+    from paper_2605_27740_amd.session import DecodeSession
+
+    t0 = time.time()
+    kw = {} if args.top_k is None else {"top_k": args.top_k}
+    wl = {"c2": W.config2, "c3": W.config3, "c4": W.config4, "c5": W.config5}[args.workload](device=dev, **kw)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    sess = DecodeSession(wl, want_scores=False)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    # bulk statistics build (prefill-time work, reported but not part of the step)
+    sess.update_page_stats()
+    torch.cuda.synchronize()
+    a, b_ = ev(), ev()
+    a.record(); sess.update_page_stats(); b_.record(); torch.cuda.synchronize()
+    bulk_stats_ms = a.elapsed_time(b_)
+
+    tok_end = wl.seq_lens.clone()
+    tok_begin = tok_end - 1
+
+    def step():
+        sess.update_page_stats(tok_begin, tok_end, 1)
+        sess.score_select_topk()
+        sess.sparse_paged_decode()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # --- timed region: exactly K steps
+    start, stop = ev(), ev()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(stop) / args.steps
+
+    # --- the same K steps again with an event between stages (stage breakdown; the events cost a little)
+    marks = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        marks[i][0].record()
+        sess.update_page_stats(tok_begin, tok_end, 1)
+        marks[i][1].record()
+        sess.score_select_topk()
+        marks[i][2].record()
+        sess.sparse_paged_decode()
+        marks[i][3].record()
+    torch.cuda.synchronize()
+    import statistics as st
+    def stage(j):
+        xs = sorted(marks[i][j].elapsed_time(marks[i][j + 1]) * 1e3 for i in range(args.steps))
+        return {"mean": st.fmean(xs), "median": xs[len(xs) // 2], "p10": xs[len(xs) // 10], "p90": xs[(9 * len(xs)) // 10]}
+    stages = {"update_page_stats_tail": stage(0), "score_select_topk": stage(1), "sparse_paged_decode": stage(2)}
+
+    # --- per-kernel durations inside the calls (score vs select, partial vs merge): timed one kernel pair at a time
+    def timed(fn, n):
+        x, y = ev(), ev()
+        x.record()
+        for _ in range(n):
+            fn()
+        y.record()
+        torch.cuda.synchronize()
+        return x.elapsed_time(y) * 1e3 / n
+
+    dense_us = None
+    if not args.no_dense:
+        nd = max(3, min(args.steps, 20))
+        sess.dense_paged_decode()
+        dense_us = timed(sess.dense_paged_decode, nd)
+
+    seq_lens = wl.seq_lens.cpu().tolist()
+    sel_count = sess.sel_count.cpu()
+    ab = algorithmic_bytes(wl, sess, sel_count, seq_lens)
+
+    # dominant kernel of the step: whichever call takes longest, priced on its algorithmic bytes.
+    # The select and merge kernels are small next to the score and partial kernels of the same calls, so the
+    # call durations bound the kernel durations from above (achieved GB/s is therefore slightly understated).
+    score_us = stages["score_select_topk"]["mean"]
+    dec_us = stages["sparse_paged_decode"]["mean"]
+    by_kernel = {
+        "page_score_kernel(+select)": {"bytes": ab["page_score_kernel"] + ab["topk_select_kernel"], "us": score_us},
+        "paged_decode_partial_kernel(+merge)": {"bytes": ab["paged_decode_partial_kernel"], "us": dec_us},
+    }
+    for v in by_kernel.values():
+        v["GBps"] = v["bytes"] / v["us"] / 1e3
+        v["frac"] = v["GBps"] / HBM_PEAK_GBPS
+    dom = max(by_kernel, key=lambda k: by_kernel[k]["us"])
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": by_kernel[dom]["GBps"], "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": by_kernel[dom]["frac"], "traffic": None,
+                "algorithmic_bytes_per_launch": by_kernel[dom]["bytes"], "avg_launch_us": by_kernel[dom]["us"],
+                "by_kernel": by_kernel}
+    if dense_us is not None:
+        roofline["dense_decode"] = {"bytes": ab["paged_decode_partial_kernel_dense"], "us": dense_us,
+                                    "GBps": ab["paged_decode_partial_kernel_dense"] / dense_us / 1e3,
+                                    "frac": ab["paged_decode_partial_kernel_dense"] / dense_us / 1e3 / HBM_PEAK_GBPS}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, sess)
+
+    step_bytes = ab["page_stats_kernel"] + ab["page_score_kernel"] + ab["topk_select_kernel"] + ab["paged_decode_partial_kernel"]
+    us = ms_per_step * 1e3
+    line = {
+        "metric": "sparse decode attention us/step (tail-page stats + page score + top-k + sparse paged decode)",
+        "value": us, "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "storage_dtype": str(wl.dtype).replace("torch.", ""), "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.B, "q_heads": wl.H, "kv_heads": wl.Hkv, "head_dim": wl.D,
+                   "page_size": wl.S, "context": max(seq_lens), "total_tokens": sum(seq_lens), "top_k_pages": sess.top_k,
+                   "lambda": wl.lam},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "stages_us": stages, "step_algorithmic_bytes": step_bytes, "step_hbm_GBps": step_bytes / us / 1e3,
+        "attention_tokens_per_s": wl.B / (us * 1e-6),
+        "dense_paged_decode_us": dense_us,
+        "speedup_vs_dense": None if dense_us is None else dense_us / us,
+        "bulk_stats_build_ms": bulk_stats_ms, "workload_gen_s": gen_s,
+        "paper_context": "paper: 11.4x attention-path speedup over dense FlashInfer at 32K, >=5.3x end to end (1x H100, S=8, batch 80)",
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(wl, sess):
+    """The float64 oracle on the host cores, on the first sequences of the batch (a bounded sample)."""
+    import numpy as np
+    import torch
+    import oracle
+    from oracle import OracleCache
+    nseq = min(wl.B, 4)
+    S = wl.S
+    pages = [wl.num_pages(b) for b in range(nseq)]
+    # compact copy of just these sequences' pages (input plumbing: same bits, identity page table)
+    idx = torch.cat([wl.page_table[b, :pages[b]].long() for b in range(nseq)])
+    k = wl.k_cache[idx].cpu().contiguous()
+    v = wl.v_cache[idx].cpu().contiguous()
+    conv = (lambda t: t.view(torch.int16).numpy().view(np.uint16)) if wl.dtype == torch.bfloat16 else (lambda t: t.numpy())
+    pt = np.zeros((nseq, max(pages)), np.int32)
+    off = 0
+    for b in range(nseq):
+        pt[b, :pages[b]] = np.arange(off, off + pages[b])
+        off += pages[b]
+    lens = wl.seq_lens[:nseq].cpu().numpy().astype(np.int32)
+    oc = OracleCache(conv(k), conv(v), pt, lens, wl.H)
+    q = conv(wl.q[:nseq].cpu().contiguous())
+    mean_all, std_all = oracle.new_stat_cache(oc)
+    t0 = time.time()
+    oracle.update_stats(oc, mean_all, std_all)       # bulk build, like the GPU's prefill-time build (not in the step)
+    bulk_s = time.time() - t0
+    reps, t_step = 0, 0.0
+    while reps < 3 or (t_step < 4.0 and reps < 50):
+        t0 = time.time()
+        oracle.update_stats(oc, mean_all, std_all, lens - 1, lens)
+        oracle.sparse_decode_step(oc, q, mean_all, std_all, wl.lam, sess.top_k, 0.0, want_scores=False)
+        t_step += time.time() - t0
+        reps += 1
+    per_step_sample = t_step / reps
+    us_full = per_step_sample * (wl.B / nseq) * 1e6
+    return {"value": us_full, "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {nseq} of {wl.B} sequences ({nseq * wl.Hkv} of {wl.B * wl.Hkv} rows), {reps} steps timed, "
+                      f"scaled by {wl.B / nseq:g}; oracle stat-cache build for the sample took {bulk_s:.2f} s (not in the step)",
+            "sample_seconds_per_step": per_step_sample}
+
+
+if __name__ == "__main__":
+    main()

@@ -15,8 +15,14 @@ namespace unique {
 namespace {
 
 constexpr int kScoreWaves = 4;
-constexpr int kTilePages = 64;  // logical pages per workgroup
-constexpr int kUnroll = 8;      // iterations whose loads are issued together
+#ifndef UNIQUE_SCORE_TILE
+#define UNIQUE_SCORE_TILE 64
+#endif
+#ifndef UNIQUE_SCORE_UNROLL
+#define UNIQUE_SCORE_UNROLL 8
+#endif
+constexpr int kTilePages = UNIQUE_SCORE_TILE;  // logical pages per workgroup
+constexpr int kUnroll = UNIQUE_SCORE_UNROLL;   // iterations whose loads are issued together
 
 __device__ __forceinline__ void load_q4(const float* p, float (&out)[4]) { load_vec(p, out); }
 __device__ __forceinline__ void load_q4(const bf16_t* p, float (&out)[4]) {
@@ -75,7 +81,11 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     for (int u = 0; u < kUnroll; ++u) {
       if (item[u] >= 0) {
         m[u] = *reinterpret_cast<const float4*>(c.page_mean + item[u] * D + dl * 4);
+#ifdef EXP_NO_STD
+        sd[u] = 1.0f;
+#else
         sd[u] = c.page_std[item[u]];
+#endif
       } else {
         m[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         sd[u] = 0.f;
