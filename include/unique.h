@@ -25,8 +25,11 @@
  *
  * Memory layout (row-major, innermost last)
  *   k_cache, v_cache : [num_phys_pages][num_kv_heads][page_size][head_dim]   dtype
- *   page_mean        : [num_phys_pages][num_kv_heads][head_dim]              float
- *   page_std         : [num_phys_pages][num_kv_heads]                        float
+ *   page_stats       : [num_phys_pages][num_kv_heads*head_dim + 32]          float
+ *                      one record per physical page: the mean vectors of its KV heads
+ *                      (head h at floats [h*D, (h+1)*D)), then the scalar stds (head h at float
+ *                      num_kv_heads*D + h), padded to 32 floats so that a page's statistics are
+ *                      one contiguous, 128-byte-aligned block; pad floats are never read or written
  *   page_table       : [batch][max_pages_per_seq]  int32, logical page -> physical page
  *   seq_lens         : [batch] int32, tokens cached per sequence INCLUDING the token being
  *                      decoded (the caller appends k_t, v_t first); must be >= 1
@@ -36,8 +39,8 @@
  *   last page may be partial. Slots beyond seq_lens[b] are never read.
  *
  * Supported shapes: dtype fp32 or bf16; head_dim 64 or 128; page_size 8, 16 or 32;
- * group size G = num_q_heads / num_kv_heads in {1, 2, 4, 8}; num_kv_heads in {1, 2, 4, 8}
- * (also 16 when head_dim is 64). Anything else returns UNIQUE_ERR_UNSUPPORTED.
+ * group size G = num_q_heads / num_kv_heads in {1, 2, 4, 8}; num_kv_heads in {1, 2, 4, 8, 16, 32}.
+ * Anything else returns UNIQUE_ERR_UNSUPPORTED.
  */
 #ifndef UNIQUE_H_
 #define UNIQUE_H_
@@ -71,8 +74,7 @@ typedef struct unique_cache_desc {
   int64_t num_phys_pages;    /* pages in the pool */
   const void* k_cache;       /* device */
   const void* v_cache;       /* device */
-  float* page_mean;          /* device, written by unique_update_page_stats, read by unique_score_select_topk */
-  float* page_std;           /* device, same */
+  float* page_stats;         /* device, written by unique_update_page_stats, read by unique_score_select_topk */
   const int32_t* page_table; /* device */
   const int32_t* seq_lens;   /* device */
 } unique_cache_desc;
@@ -82,11 +84,14 @@ typedef struct unique_cache_desc {
  * The contents need no initialisation and carry nothing between calls. */
 int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t* out_bytes);
 
+/* Floats per page record of page_stats for this descriptor (num_kv_heads*head_dim + 32); 0 if desc is NULL. */
+int64_t unique_page_stats_stride(const unique_cache_desc* desc);
+
 /* Page statistics, Eq. 1 (mean over the page's keys, per dimension) and Eq. 2 (per-dimension
  * population standard deviation collapsed by its l2 norm into one scalar), recomputed from the
  * keys in the cache for every logical page of sequence b that overlaps the token range
  * [d_tok_begin[b], d_tok_end[b]) (clamped to [0, seq_lens[b])), for every KV head. A partial last
- * page uses its valid tokens only. Results go to page_mean / page_std at the page's PHYSICAL index.
+ * page uses its valid tokens only. Results go to the page's record in page_stats (PHYSICAL page index).
  *   d_tok_begin, d_tok_end : device int32 [batch], or both NULL = every page of every sequence.
  *   max_pages_touched_per_seq : host upper bound on pages overlapped per sequence (sizes the grid;
  *                               pages beyond it are NOT refreshed); ignored when the ranges are NULL.

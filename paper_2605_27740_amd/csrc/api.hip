@@ -50,20 +50,18 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
       !unique::score_supported(d->dtype, d->head_dim, G, d->num_kv_heads) ||
       !unique::decode_supported(d->dtype, d->head_dim, d->page_size, G))
     return fail(UNIQUE_ERR_UNSUPPORTED, "shape not compiled: dtype=%d head_dim=%d page_size=%d G=%d num_kv_heads=%d "
-                "(supported: head_dim 64|128, page_size 8|16|32, G 1|2|4|8, num_kv_heads 1|2|4|8, or 16 at head_dim 64)",
+                "(supported: head_dim 64|128, page_size 8|16|32, G 1|2|4|8, num_kv_heads 1|2|4|8|16|32)",
                 d->dtype, d->head_dim, d->page_size, G, d->num_kv_heads);
   if (!d->k_cache || !d->page_table || !d->seq_lens)
     return fail(UNIQUE_ERR_INVALID_ARG, "k_cache, page_table and seq_lens must be non-NULL");
   if (need_v && !d->v_cache) return fail(UNIQUE_ERR_INVALID_ARG, "v_cache is NULL");
-  if (need_stats && (!d->page_mean || !d->page_std))
-    return fail(UNIQUE_ERR_INVALID_ARG, "page_mean and page_std must be non-NULL");
-  const uintptr_t misaligned = (uintptr_t)d->k_cache | (uintptr_t)d->v_cache | (uintptr_t)d->page_mean;
-  if (misaligned & 15u) return fail(UNIQUE_ERR_INVALID_ARG, "k_cache, v_cache and page_mean must be 16-byte aligned");
+  if (need_stats && !d->page_stats) return fail(UNIQUE_ERR_INVALID_ARG, "page_stats must be non-NULL");
+  const uintptr_t misaligned = (uintptr_t)d->k_cache | (uintptr_t)d->v_cache | (uintptr_t)d->page_stats;
+  if (misaligned & 15u) return fail(UNIQUE_ERR_INVALID_ARG, "k_cache, v_cache and page_stats must be 16-byte aligned");
 
   v->k_cache = d->k_cache;
   v->v_cache = d->v_cache;
-  v->page_mean = d->page_mean;
-  v->page_std = d->page_std;
+  v->page_stats = d->page_stats;
   v->page_table = d->page_table;
   v->seq_lens = d->seq_lens;
   v->H = d->num_q_heads;
@@ -116,7 +114,7 @@ int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t*
   if (!d.page_table) d.page_table = dummy;
   if (!d.seq_lens) d.seq_lens = dummy;
   d.v_cache = nullptr;
-  d.page_mean = nullptr;
+  d.page_stats = nullptr;
   unique::CacheView v;
   const int rc = make_view(&d, &v, false, false);
   if (rc != UNIQUE_OK) return rc;
@@ -127,6 +125,11 @@ int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t*
   if (de > need) need = de;
   *out_bytes = round_up(need, kAlign);
   return UNIQUE_OK;
+}
+
+int64_t unique_page_stats_stride(const unique_cache_desc* desc) {
+  if (!desc) return 0;
+  return (int64_t)desc->num_kv_heads * desc->head_dim + unique::kStdBlock;
 }
 
 int unique_update_page_stats(const unique_cache_desc* desc, const int32_t* d_tok_begin, const int32_t* d_tok_end,

@@ -292,7 +292,7 @@ bool decode_supported(int dtype, int D, int S, int G) {
 SplitPlan plan_splits(int rows, int max_list_len) {
   // aim at ~4 workgroups (16 waves) per CU of a 256-CU device, with at least 2 pages per wave
 #ifndef UNIQUE_DEC_TARGET_GROUPS
-#define UNIQUE_DEC_TARGET_GROUPS 1024
+#define UNIQUE_DEC_TARGET_GROUPS 512
 #endif
   constexpr int kTargetGroups = UNIQUE_DEC_TARGET_GROUPS;
   if (rows < 1) rows = 1;

@@ -9,8 +9,7 @@ namespace unique {
 struct CacheView {
   const void* k_cache;        // [num_phys][Hkv][S][D]
   const void* v_cache;
-  float* page_mean;           // [num_phys][Hkv][D]
-  float* page_std;            // [num_phys][Hkv]
+  float* page_stats;          // [num_phys][Hkv*D + kStdBlock]: means of all heads, then stds, then pad
   const int32_t* page_table;  // [B][max_pages]
   const int32_t* seq_lens;    // [B]
   int32_t H, Hkv, D, S, B, max_pages;
@@ -26,6 +25,7 @@ struct SplitPlan {
 };
 SplitPlan plan_splits(int rows, int max_list_len);
 
+constexpr int kStdBlock = 32;          // floats reserved after the means of a page record (stds + pad)
 constexpr int kScoreStrideAlign = 64;  // score rows in the workspace are padded to this many floats
 
 bool stats_supported(int dtype, int D, int S);

@@ -1,13 +1,16 @@
 // Fused page-score kernel (Eq. 6 of the paper; Eq. 3 when G = 1):
 //   score(p) = max_g [ q_g . mean_p + lambda * |q_g|_2 * std_p ]   per (sequence, KV head, logical page).
-// The G x P intermediate never exists in memory: each group of D/4 lanes holds one page-head mean
-// (one 16-byte chunk per lane), keeps its G query slices in registers for the whole kernel,
-// reduces the G dot products across the lane group, applies the offset and the max, and writes one float.
+// The G x P intermediate never exists in memory: the G dot products, the rank-one offset and the max
+// over the group are all formed in registers and one float per (KV head, page) is written.
 //
-// A workgroup of 4 waves walks a tile of consecutive logical pages of one sequence. The lane groups
-// of the workgroup are laid over (page, KV head) so that, for one page, all KV heads are read as one
-// contiguous Hkv*D*4-byte block even when the page table scatters pages over the pool. Page-table
-// entries for several iterations are fetched ahead of the mean loads that depend on them.
+// Layout of the work: 8 lanes own one (page, KV head) mean row and read it as D/32 16-byte chunks
+// each, so a wave covers 8 consecutive head rows per step -- with 8 KV heads that is exactly one
+// page record, read as one contiguous block whatever the page table does to page placement, with
+// the page's stds taken from the tail of the same record. Every lane keeps its slices of the G
+// queries of its (fixed) KV head in registers for the whole kernel. The G partial dot products are
+// reduced over the 8 lanes with three DPP steps. Page-table entries for several steps are fetched
+// ahead of the record loads that depend on them. Scores of a tile are staged in LDS and written as
+// one contiguous run per KV head (4-byte scattered stores cost a tenth of the kernel otherwise).
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -19,10 +22,12 @@ constexpr int kScoreWaves = 4;
 #define UNIQUE_SCORE_TILE 64
 #endif
 #ifndef UNIQUE_SCORE_UNROLL
-#define UNIQUE_SCORE_UNROLL 8
+#define UNIQUE_SCORE_UNROLL 2
 #endif
 constexpr int kTilePages = UNIQUE_SCORE_TILE;  // logical pages per workgroup
-constexpr int kUnroll = UNIQUE_SCORE_UNROLL;   // iterations whose loads are issued together
+constexpr int kMaxKvHeads = 32;
+constexpr int kRowLanes = 8;                   // lanes per (page, head) row
+constexpr int kRowsPerWave = kWave / kRowLanes;
 
 __device__ __forceinline__ void load_q4(const float* p, float (&out)[4]) { load_vec(p, out); }
 __device__ __forceinline__ void load_q4(const bf16_t* p, float (&out)[4]) {
@@ -36,58 +41,77 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
                                                                         float lambda, float* __restrict__ scores,
                                                                         int score_stride,
                                                                         float* __restrict__ scores_out) {
-  constexpr int kLanesPerHead = D / 4;                  // lanes covering one fp32 mean vector
-  constexpr int kSlotsPerWave = kWave / kLanesPerHead;  // (page, head) items per wave-wide load
-  constexpr int kSlots = kScoreWaves * kSlotsPerWave;   // items per workgroup iteration
+  constexpr int kChunks = D / (4 * kRowLanes);  // 16-byte loads per lane per row
+  constexpr int kUnroll = (G * kChunks > 16) ? (UNIQUE_SCORE_UNROLL / 2 > 0 ? UNIQUE_SCORE_UNROLL / 2 : 1)
+                                             : UNIQUE_SCORE_UNROLL;
 
   const int b = blockIdx.y;
   const int N = c.seq_lens[b];
   const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
   const int tile0 = blockIdx.x * kTilePages;
   if (tile0 >= P) return;
+  const int tile_end = min(tile0 + kTilePages, P);
 
-  const int lane = threadIdx.x % kWave;
-  const int dl = lane % kLanesPerHead;
-  const int slot = (threadIdx.x / kWave) * kSlotsPerWave + lane / kLanesPerHead;
-  const int hkv = slot % c.Hkv;        // fixed for the whole kernel because kSlots % Hkv == 0
-  const int page_in_iter = slot / c.Hkv;
-  const int pages_per_iter = kSlots / c.Hkv;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int row8 = lane / kRowLanes, cl = lane % kRowLanes;
+  // which head and which page of a step this lane's row is; both fixed for the whole kernel
+  int hkv, page_in_step, pages_per_step, wave_slot, wave_slots;
+  if (c.Hkv >= kRowsPerWave) {
+    const int slots_per_page = c.Hkv / kRowsPerWave;  // a page record spans this many wave steps
+    hkv = (wave % slots_per_page) * kRowsPerWave + row8;
+    page_in_step = 0;
+    pages_per_step = 1;
+    wave_slot = wave / slots_per_page;
+    wave_slots = kScoreWaves / slots_per_page;
+  } else {
+    pages_per_step = kRowsPerWave / c.Hkv;
+    hkv = row8 % c.Hkv;
+    page_in_step = row8 / c.Hkv;
+    wave_slot = wave;
+    wave_slots = kScoreWaves;
+  }
 
-  // this lane's slice of the G queries of its KV head, and lambda * |q_g|
-  float qv[G][4];
+  float qv[G][kChunks][4];
   float off[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    load_q4(q + ((int64_t)b * c.H + hkv * G + g) * D + dl * 4, qv[g]);
-    float qq = qv[g][0] * qv[g][0] + qv[g][1] * qv[g][1] + qv[g][2] * qv[g][2] + qv[g][3] * qv[g][3];
-    qq = group_allreduce<kLanesPerHead>(qq, OpSum());
+    float qq = 0.f;
+#pragma unroll
+    for (int j = 0; j < kChunks; ++j) {
+      load_q4(q + ((int64_t)b * c.H + hkv * G + g) * D + j * (4 * kRowLanes) + cl * 4, qv[g][j]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) qq = fmaf(qv[g][j][i], qv[g][j][i], qq);
+    }
+    qq = group_allreduce<kRowLanes>(qq, OpSum());
     off[g] = lambda * sqrtf(qq);
   }
 
   const int32_t* pt = c.page_table + (int64_t)b * c.max_pages;
-  const int tile_end = min(tile0 + kTilePages, P);
-  for (int p0 = tile0 + page_in_iter; p0 < tile_end + page_in_iter; p0 += pages_per_iter * kUnroll) {
-    int64_t item[kUnroll];
+  const int64_t rec_stride = (int64_t)c.Hkv * D + kStdBlock;
+  const int step_pages = wave_slots * pages_per_step;  // pages the workgroup advances per step
+  __shared__ float tile_scores[kMaxKvHeads][kTilePages];
+
+  for (int base = tile0 + wave_slot * pages_per_step; base < tile_end; base += step_pages * kUnroll) {
+    const float* rec[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const int p = p0 + u * pages_per_iter;
+      const int p = base + u * step_pages + page_in_step;
       int64_t phys = -1;
       if (p < tile_end) phys = pt[p];
-      item[u] = (phys >= 0 && phys < c.num_phys) ? phys * c.Hkv + hkv : -1;
+      rec[u] = (phys >= 0 && phys < c.num_phys) ? c.page_stats + phys * rec_stride : nullptr;
     }
-    float4 m[kUnroll];
+    float4 m[kUnroll][kChunks];
     float sd[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      if (item[u] >= 0) {
-        m[u] = *reinterpret_cast<const float4*>(c.page_mean + item[u] * D + dl * 4);
-#ifdef EXP_NO_STD
-        sd[u] = 1.0f;
-#else
-        sd[u] = c.page_std[item[u]];
-#endif
+      if (rec[u]) {
+#pragma unroll
+        for (int j = 0; j < kChunks; ++j)
+          m[u][j] = *reinterpret_cast<const float4*>(rec[u] + hkv * D + j * (4 * kRowLanes) + cl * 4);
+        sd[u] = rec[u][c.Hkv * D + hkv];
       } else {
-        m[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < kChunks; ++j) m[u][j] = make_float4(0.f, 0.f, 0.f, 0.f);
         sd[u] = 0.f;
       }
     }
@@ -96,19 +120,32 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
       float best = 0.f;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float dot = qv[g][0] * m[u].x;
-        dot = fmaf(qv[g][1], m[u].y, dot);
-        dot = fmaf(qv[g][2], m[u].z, dot);
-        dot = fmaf(qv[g][3], m[u].w, dot);
-        dot = group_allreduce<kLanesPerHead>(dot, OpSum());
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < kChunks; ++j) {
+          dot = fmaf(qv[g][j][0], m[u][j].x, dot);
+          dot = fmaf(qv[g][j][1], m[u][j].y, dot);
+          dot = fmaf(qv[g][j][2], m[u][j].z, dot);
+          dot = fmaf(qv[g][j][3], m[u][j].w, dot);
+        }
+        dot = group_allreduce<kRowLanes>(dot, OpSum());
         const float s = fmaf(off[g], sd[u], dot);
         best = (g == 0) ? s : fmaxf(best, s);
       }
-      const int p = p0 + u * pages_per_iter;
-      if (dl == 0 && item[u] >= 0) {
-        scores[((int64_t)b * c.Hkv + hkv) * score_stride + p] = best;
-        if (scores_out) scores_out[((int64_t)b * c.Hkv + hkv) * c.max_pages + p] = best;
-      }
+      const int p = base + u * step_pages + page_in_step;
+      // a page whose table entry points outside the pool gets NaN, which ranks below every score
+      if (cl == 0 && p < tile_end) tile_scores[hkv][p - tile0] = rec[u] ? best : __uint_as_float(0x7fc00000u);
+    }
+  }
+  __syncthreads();
+  // the tile's scores leave as one contiguous run per KV head
+  const int tile_len = tile_end - tile0;
+  for (int idx = threadIdx.x; idx < c.Hkv * kTilePages; idx += kScoreWaves * kWave) {
+    const int h = idx / kTilePages, pp = idx % kTilePages;
+    if (pp < tile_len) {
+      const float v = tile_scores[h][pp];
+      scores[((int64_t)b * c.Hkv + h) * score_stride + tile0 + pp] = v;
+      if (scores_out) scores_out[((int64_t)b * c.Hkv + h) * c.max_pages + tile0 + pp] = v;
     }
   }
 }
@@ -138,8 +175,8 @@ hipError_t dispatch_g(const CacheView& c, const void* q, float lambda, float* sc
 bool score_supported(int dtype, int D, int G, int Hkv) {
   if (!(dtype == 0 || dtype == 1) || !(D == 64 || D == 128)) return false;
   if (!(G == 1 || G == 2 || G == 4 || G == 8)) return false;
-  const int slots = kScoreWaves * (kWave / (D / 4));
-  return Hkv >= 1 && Hkv <= slots && slots % Hkv == 0;
+  // a wave covers 8 head rows per step; the 4 waves of a workgroup must tile whole page records
+  return Hkv == 1 || Hkv == 2 || Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv == 32;
 }
 
 hipError_t launch_score(const CacheView& c, const void* d_q, float lambda, float* d_scores, int score_stride,

@@ -1,16 +1,26 @@
 // Top-k page selection per (sequence, KV head) row (Section 3.2 of the paper, radix-based top-k).
 //
-// One workgroup per row. Scores become order-preserving 32-bit keys held in registers (a row of up to
-// 32768 pages fits a 1024-thread workgroup at 32 keys per thread); four rounds of 8-bit radix selection
-// over an LDS histogram narrow the k-th largest key exactly; a final index-ordered compaction emits
-// the selected logical pages in ascending order, taking tied keys from the lowest page index upward.
-// The paper selects over bf16 scores in two rounds; fp32 keys in four rounds are used here so that
-// the chosen set equals an exact ranking of the fp32 scores.
+// One workgroup per row; the row's scores are read once and stay in registers as order-preserving
+// 32-bit keys. The paper narrows the k-th largest score with two 8-bit radix rounds over bf16 scores;
+// here the scores are fp32 and the selected set has to equal an exact ranking, so the search is:
+//   1. one histogram pass over 2 * threads buckets that are LINEAR in the score between the row's
+//      minimum and maximum (a monotone map, so bucket order never contradicts score order). It finds
+//      the bucket holding the k-th largest score; everything in higher buckets is selected. Linear
+//      buckets spread page scores far better than the leading bits of a float (which are mostly
+//      exponent), so LDS atomics see little same-address contention and the boundary bucket holds
+//      only a handful of candidates.
+//   2. exact resolution among the candidates of the boundary bucket: by pairwise ranking on
+//      (key, page index) when they are few, otherwise by four 8-bit radix rounds over their keys
+//      (this also covers degenerate rows such as all scores equal).
+//   3. an index-ordered compaction (one workgroup scan) that emits the selected logical pages in
+//      ascending order and takes keys tied with the k-th from the lowest page index upward.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
 namespace unique {
 namespace {
+
+constexpr int kMaxRankCandidates = 512;  // above this the boundary bucket is resolved by radix rounds
 
 template <int kThreads>
 __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long v,
@@ -29,74 +39,29 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
   return base + inc - v;
 }
 
-// kItems > 0: keys of the row live in registers, kItems per thread. kItems == 0: the row is too long
-// for that, and every pass re-reads the scores (they stay in L2).
-template <int kThreads, int kItems>
-__global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, const float* __restrict__ scores,
-                                                               int score_stride, int top_k,
-                                                               int32_t* __restrict__ sel_pages,
-                                                               int32_t* __restrict__ sel_count) {
-  __shared__ int hist[256];
-  __shared__ unsigned long long wave_tot[kThreads / kWave];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_need;
+__device__ __forceinline__ float ordered_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
 
-  const int row = blockIdx.x;
-  const int b = row / c.Hkv;
-  const int N = c.seq_lens[b];
-  int P = min((N + c.S - 1) / c.S, c.max_pages_hint);
-  if (kItems > 0) P = min(P, kThreads * kItems);  // a row longer than the host bound is cut, never overrun
-  const int kb = min(top_k, P);
+// One round-set of 8-bit radix selection over the keys accepted by `keep(j)`: returns the exact key of
+// the need-th largest accepted key and leaves in `need` how many keys equal to it must be taken.
+// hist: 256 ints of LDS; s_prefix / s_need: LDS scalars. All threads of the workgroup must call it.
+// kStatic > 0: the per-thread item count is that constant (items live in registers, loops unroll).
+template <int kThreads, int kStatic, typename KeyAt, typename Keep>
+__device__ __forceinline__ uint32_t radix_threshold(int n_items, KeyAt key_at, Keep keep, int& need, int* hist,
+                                                    uint32_t* s_prefix, int* s_need) {
   const int t = threadIdx.x;
-  int32_t* out = sel_pages + (int64_t)row * top_k;
-  const float* srow = scores + (int64_t)row * score_stride;
-
-  for (int i = kb + t; i < top_k; i += kThreads) out[i] = -1;
-  if (t == 0) sel_count[row] = kb;
-  if (kb == P) {  // everything is selected
-    for (int i = t; i < P; i += kThreads) out[i] = i;
-    return;
-  }
-
-  const int ipt = kItems > 0 ? kItems : (P + kThreads - 1) / kThreads;
-  const int first = t * ipt;
-  const int nv = max(0, min(ipt, P - first));  // valid items of this thread
-
-  uint32_t key[kItems > 0 ? kItems : 1];
-  if constexpr (kItems >= 4) {
-#pragma unroll
-    for (int j = 0; j < kItems; j += 4) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (j < nv) v = *reinterpret_cast<const float4*>(srow + first + j);  // row stride is padded past P
-      key[j] = float_to_ordered(v.x); key[j + 1] = float_to_ordered(v.y);
-      key[j + 2] = float_to_ordered(v.z); key[j + 3] = float_to_ordered(v.w);
-    }
-  } else if constexpr (kItems > 0) {
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) key[j] = j < nv ? float_to_ordered(srow[first + j]) : 0u;
-  }
-  auto key_at = [&](int j) -> uint32_t {
-    if constexpr (kItems > 0) return key[j];
-    else return float_to_ordered(srow[first + j]);
-  };
-
+  const int n = kStatic > 0 ? kStatic : n_items;
   uint32_t prefix = 0;
-  int need = kb;
 #pragma unroll 1
   for (int round = 0; round < 4; ++round) {
     const int shift = 24 - 8 * round;
+    __syncthreads();  // everyone is done with the previous contents of hist
     if (t < 256) hist[t] = 0;
     __syncthreads();
-    if constexpr (kItems > 0) {
 #pragma unroll
-      for (int j = 0; j < kItems; ++j) {
-        if (j < nv) {
-          const uint32_t k = key[j];
-          if (round == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
-        }
-      }
-    } else {
-      for (int j = 0; j < nv; ++j) {
+    for (int j = 0; j < n; ++j) {
+      if (keep(j)) {
         const uint32_t k = key_at(j);
         if (round == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
       }
@@ -117,45 +82,236 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
 #pragma unroll
       for (int i = 3; i >= 0; --i) {
         if (above < need && need <= above + cnt[i]) {
-          s_prefix = (prefix << 8) | (uint32_t)(4 * t + i);
-          s_need = need - above;
+          *s_prefix = (prefix << 8) | (uint32_t)(4 * t + i);
+          *s_need = need - above;
         }
         above += cnt[i];
       }
     }
     __syncthreads();
-    prefix = s_prefix;
-    need = s_need;
+    prefix = *s_prefix;
+    need = *s_need;
   }
-  // prefix is now the exact key of the kb-th largest score; `need` keys equal to it are taken.
-  uint32_t gt = 0, eq = 0;
-  if constexpr (kItems > 0) {
+  return prefix;
+}
+
+// kItems keys per thread in registers (blocked: thread t owns pages [t*kItems, (t+1)*kItems)).
+template <int kThreads, int kItems>
+__global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, const float* __restrict__ scores,
+                                                               int score_stride, int top_k,
+                                                               int32_t* __restrict__ sel_pages,
+                                                               int32_t* __restrict__ sel_count) {
+  constexpr int kWaves = kThreads / kWave;
+  constexpr int kBuckets = 2 * kThreads;
+  constexpr int kMaxRank = kThreads < kMaxRankCandidates ? kThreads : kMaxRankCandidates;
+  __shared__ int hist[kBuckets];
+  __shared__ unsigned long long wave_tot[kWaves];
+  __shared__ uint32_t wave_min[kWaves], wave_max[kWaves];
+  __shared__ uint32_t cand_key[kMaxRank];
+  __shared__ int cand_idx[kMaxRank];
+  __shared__ int s_bucket, s_need, s_ncand;
+  __shared__ uint32_t s_prefix;
+
+  const int row = blockIdx.x;
+  const int b = row / c.Hkv;
+  const int N = c.seq_lens[b];
+  int P = min((N + c.S - 1) / c.S, c.max_pages_hint);
+  P = min(P, kThreads * kItems);  // a row longer than the host bound is cut, never overrun
+  const int kb = min(top_k, P);
+  const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+  int32_t* out = sel_pages + (int64_t)row * top_k;
+  const float* srow = scores + (int64_t)row * score_stride;
+
+  for (int i = kb + t; i < top_k; i += kThreads) out[i] = -1;
+  if (t == 0) sel_count[row] = kb;
+  if (kb == P) {  // everything is selected
+    for (int i = t; i < P; i += kThreads) out[i] = i;
+    return;
+  }
+
+  const int first = t * kItems;
+  const int nv = max(0, min(kItems, P - first));  // valid items of this thread
+
+  uint32_t key[kItems];
+  if constexpr (kItems >= 4) {
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-      if (j < nv) { gt += key[j] > prefix; eq += key[j] == prefix; }
+    for (int j = 0; j < kItems; j += 4) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < nv) v = *reinterpret_cast<const float4*>(srow + first + j);  // row stride is padded past P
+      key[j] = float_to_ordered(v.x); key[j + 1] = float_to_ordered(v.y);
+      key[j + 2] = float_to_ordered(v.z); key[j + 3] = float_to_ordered(v.w);
     }
   } else {
-    for (int j = 0; j < nv; ++j) { const uint32_t k = key_at(j); gt += k > prefix; eq += k == prefix; }
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) key[j] = j < nv ? float_to_ordered(srow[first + j]) : 0u;
   }
-  // one scan carries both counters: keys above the threshold (low half) and keys equal to it (high half)
+
+  // ---- 1. linear-bucket histogram between the row's smallest and largest finite score
+  constexpr uint32_t kKeyNegInf = 0x007fffffu, kKeyPosInf = 0xff800000u;  // keys of -inf and +inf
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (j < nv && key[j] > kKeyNegInf && key[j] < kKeyPosInf) { kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
+  }
+  if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+  for (int i = t; i < kBuckets; i += kThreads) hist[i] = 0;
+  if (t == 0) s_ncand = 0;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+  float lo = 0.f, scale = 0.f;
+  if (kmin < kmax) {  // at least two distinct finite scores
+    lo = ordered_to_float(kmin);
+    const float range = ordered_to_float(kmax) - lo;
+    if (range > 0.f && range < 3.0e38f) scale = (float)(kBuckets - 1) / range;
+    if (!(scale < 3.0e38f)) scale = 0.f;  // a denormal range: leave everything in one bucket
+  }
+  int bucket[kItems];
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    int bk = 0;
+    if (j < nv) {
+      const uint32_t k = key[j];
+      if (k >= kKeyPosInf) bk = kBuckets - 1;  // +inf
+      else if (k > kKeyNegInf) {                // finite: monotone in the score
+        const float x = (ordered_to_float(k) - lo) * scale;
+        bk = min(kBuckets - 1, max(0, (int)x));
+      }                                         // -inf and NaN stay in bucket 0
+      atomicAdd(&hist[bk], 1);
+    }
+    bucket[j] = bk;
+  }
+  __syncthreads();
+  {  // suffix scan over the buckets: thread t owns buckets kBuckets-1-2t and kBuckets-2-2t
+    const int c_hi = hist[kBuckets - 1 - 2 * t], c_lo = hist[kBuckets - 2 - 2 * t];
+    int above = (int)block_exclusive_scan<kThreads>((unsigned long long)(c_hi + c_lo), wave_tot);
+    if (above < kb && kb <= above + c_hi) { s_bucket = kBuckets - 1 - 2 * t; s_need = kb - above; }
+    above += c_hi;
+    if (above < kb && kb <= above + c_lo) { s_bucket = kBuckets - 2 - 2 * t; s_need = kb - above; }
+  }
+  __syncthreads();
+  const int bstar = s_bucket;
+  int need = s_need;  // how many of the boundary bucket's keys are selected
+  const int ncand = hist[bstar];
+
+  // ---- 2. exact threshold inside the boundary bucket: key T and how many keys equal to T to take
+  uint32_t T;
+  if (ncand <= kMaxRank) {
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      if (j < nv && bucket[j] == bstar) {
+        const int slot = atomicAdd(&s_ncand, 1);
+        cand_key[slot] = key[j];
+        cand_idx[slot] = first + j;
+      }
+    }
+    __syncthreads();
+    if (t < ncand) {
+      const uint32_t mk = cand_key[t];
+      const int mi = cand_idx[t];
+      int rank = 0, greater = 0;
+      for (int j = 0; j < ncand; ++j) {
+        const uint32_t k = cand_key[j];
+        greater += k > mk;
+        rank += (k > mk) || (k == mk && cand_idx[j] < mi);
+      }
+      if (rank == need - 1) { s_prefix = mk; s_need = need - greater; }
+    }
+    __syncthreads();
+    T = s_prefix;
+    need = s_need;
+  } else {
+    T = radix_threshold<kThreads, kItems>(
+        kItems, [&](int j) { return key[j]; }, [&](int j) { return j < nv && bucket[j] == bstar; }, need, hist,
+        &s_prefix, &s_need);
+  }
+
+  // ---- 3. index-ordered compaction. "sure": above the boundary; "tie": equal to the k-th key.
+  uint32_t sure = 0, tie = 0;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (j < nv) {
+      const bool in_b = bucket[j] == bstar;
+      sure += (bucket[j] > bstar) || (in_b && key[j] > T);
+      tie += in_b && key[j] == T;
+    }
+  }
+  const unsigned long long before =
+      block_exclusive_scan<kThreads>((unsigned long long)sure | ((unsigned long long)tie << 32), wave_tot);
+  int sure_b = (int)(before & 0xffffffffull), tie_b = (int)(before >> 32);
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (j < nv) {
+      const bool in_b = bucket[j] == bstar;
+      if ((bucket[j] > bstar) || (in_b && key[j] > T)) {
+        out[sure_b + min(tie_b, need)] = first + j;
+        ++sure_b;
+      } else if (in_b && key[j] == T) {
+        if (tie_b < need) out[sure_b + tie_b] = first + j;
+        ++tie_b;
+      }
+    }
+  }
+}
+
+// Rows too long for registers: every pass re-reads the scores (they stay in L2). Plain four-round
+// radix selection over the 32-bit keys, then the same index-ordered compaction.
+template <int kThreads>
+__global__ __launch_bounds__(kThreads) void topk_select_long_kernel(CacheView c, const float* __restrict__ scores,
+                                                                    int score_stride, int top_k,
+                                                                    int32_t* __restrict__ sel_pages,
+                                                                    int32_t* __restrict__ sel_count) {
+  __shared__ int hist[256];
+  __shared__ unsigned long long wave_tot[kThreads / kWave];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+
+  const int row = blockIdx.x;
+  const int b = row / c.Hkv;
+  const int N = c.seq_lens[b];
+  const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);
+  const int kb = min(top_k, P);
+  const int t = threadIdx.x;
+  int32_t* out = sel_pages + (int64_t)row * top_k;
+  const float* srow = scores + (int64_t)row * score_stride;
+
+  for (int i = kb + t; i < top_k; i += kThreads) out[i] = -1;
+  if (t == 0) sel_count[row] = kb;
+  if (kb == P) {
+    for (int i = t; i < P; i += kThreads) out[i] = i;
+    return;
+  }
+  const int ipt = (P + kThreads - 1) / kThreads;
+  const int first = t * ipt;
+  const int nv = max(0, min(ipt, P - first));
+  auto key_at = [&](int j) { return float_to_ordered(srow[first + j]); };
+
+  int need = kb;
+  const uint32_t T = radix_threshold<kThreads, 0>(nv, key_at, [&](int) { return true; }, need, hist, &s_prefix, &s_need);
+
+  uint32_t gt = 0, eq = 0;
+  for (int j = 0; j < nv; ++j) {
+    const uint32_t k = key_at(j);
+    gt += k > T;
+    eq += k == T;
+  }
   const unsigned long long before =
       block_exclusive_scan<kThreads>((unsigned long long)gt | ((unsigned long long)eq << 32), wave_tot);
   int gt_b = (int)(before & 0xffffffffull), eq_b = (int)(before >> 32);
-  auto emit = [&](int j) {
+  for (int j = 0; j < nv; ++j) {
     const uint32_t k = key_at(j);
-    if (k > prefix) {
+    if (k > T) {
       out[gt_b + min(eq_b, need)] = first + j;
       ++gt_b;
-    } else if (k == prefix) {
+    } else if (k == T) {
       if (eq_b < need) out[gt_b + eq_b] = first + j;
       ++eq_b;
     }
-  };
-  if constexpr (kItems > 0) {
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) if (j < nv) emit(j);
-  } else {
-    for (int j = 0; j < nv; ++j) emit(j);
   }
 }
 
@@ -178,8 +334,9 @@ hipError_t launch_select(const CacheView& c, const float* d_scores, int score_st
   if (P <= 8192) return launch_t<1024, 8>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 16384) return launch_t<1024, 16>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 32768) return launch_t<1024, 32>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
-  // longer rows do not fit in registers: every pass re-reads the scores
-  return launch_t<1024, 0>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
+  topk_select_long_kernel<1024><<<dim3(c.B * c.Hkv), dim3(1024), 0, stream>>>(c, d_scores, score_stride, top_k,
+                                                                              d_sel_pages, d_sel_count);
+  return hipGetLastError();
 }
 
 }  // namespace unique

@@ -1,5 +1,6 @@
 // Page statistics kernel (Eq. 1 and Eq. 2 of the paper): per (physical page, KV head) the mean key
-// and the scalar standard deviation (l2 norm of the per-dimension population std).
+// and the scalar standard deviation (l2 norm of the per-dimension population std), written into the
+// page's record of the statistics cache (means of all heads, then their stds, contiguous per page).
 //
 // One wavefront owns one (sequence, logical page, KV head). The page's S x D keys are one contiguous
 // block; each lane reads 16-byte chunks so that every load instruction of the wave covers a
@@ -82,13 +83,14 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
   }
   ss = group_allreduce<kWave>(ss, OpSum());
 
+  float* rec = c.page_stats + phys * ((int64_t)c.Hkv * D + kStdBlock);  // this page's record
   if (tr == 0) {
-    float* m = c.page_mean + (phys * c.Hkv + hkv) * (int64_t)D + ch * kVec;
+    float* m = rec + hkv * D + ch * kVec;
 #pragma unroll
     for (int i = 0; i < kVec; i += 4)
       *reinterpret_cast<float4*>(m + i) = make_float4(mean[i], mean[i + 1], mean[i + 2], mean[i + 3]);
   }
-  if (lane == 0) c.page_std[phys * c.Hkv + hkv] = sqrtf(ss * inv_n);
+  if (lane == 0) rec[c.Hkv * D + hkv] = sqrtf(ss * inv_n);
 }
 
 template <typename T, int D>

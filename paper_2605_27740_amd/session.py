@@ -18,12 +18,15 @@ class DecodeSession:
         self.top_k = int(top_k if top_k is not None else wl.top_k)
         dev = wl.k_cache.device
         P = wl.num_phys_pages
-        self.page_mean = torch.full((P, wl.Hkv, wl.D), float("nan"), device=dev, dtype=torch.float32)
-        self.page_std = torch.full((P, wl.Hkv), float("nan"), device=dev, dtype=torch.float32)
+        self.page_stats = torch.full((P, wl.Hkv * wl.D + binding.STD_BLOCK), float("nan"), device=dev,
+                                     dtype=torch.float32)
+        # views into the records: means [P, Hkv, D] and stds [P, Hkv]
+        self.page_mean = self.page_stats[:, :wl.Hkv * wl.D].view(P, wl.Hkv, wl.D)
+        self.page_std = self.page_stats[:, wl.Hkv * wl.D:wl.Hkv * wl.D + wl.Hkv]
         if max_seq_len_hint is None:
             max_seq_len_hint = int(wl.seq_lens.max().item()) + int(wl.meta.get("spare_tokens", 0))
         self.desc = binding.make_desc(q_heads=wl.H, k_cache=wl.k_cache, v_cache=wl.v_cache,
-                                      page_mean=self.page_mean, page_std=self.page_std,
+                                      page_stats=self.page_stats,
                                       page_table=wl.page_table, seq_lens=wl.seq_lens,
                                       max_seq_len_hint=max_seq_len_hint)
         self.sel_pages = torch.full((wl.B, wl.Hkv, self.top_k), -7, device=dev, dtype=torch.int32)
@@ -34,6 +37,7 @@ class DecodeSession:
         self.lse = torch.zeros((wl.B, wl.H), device=dev, dtype=torch.float32)
         self.out_dense = torch.zeros_like(self.out)
         self.lse_dense = torch.zeros_like(self.lse)
+        assert self.lib.page_stats_stride(self.desc) == self.page_stats.shape[1]
         self.workspace_bytes = self.lib.workspace_bytes(self.desc, self.top_k)
         self.workspace = torch.empty((max(self.workspace_bytes, 256),), device=dev, dtype=torch.uint8)
         assert self.workspace.data_ptr() % 256 == 0

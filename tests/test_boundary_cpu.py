@@ -21,7 +21,7 @@ def good_desc(**over):
     # pointers only need to be non-NULL and aligned for validation; nothing dereferences them on the host
     d = dict(dtype=1, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, batch=2,
              max_pages_per_seq=64, max_seq_len_hint=0, num_phys_pages=128, k_cache=0x1000, v_cache=0x2000,
-             page_mean=0x3000, page_std=0x4000, page_table=0x5000, seq_lens=0x6000)
+             page_stats=0x3000, page_table=0x5000, seq_lens=0x6000)
     d.update(over)
     return CacheDesc(**d)
 
@@ -34,13 +34,14 @@ def test_exports_match_header(lib):
         assert hasattr(lib.c, name)
     assert lib.version().startswith("unique-gfx950")
     assert lib.status_string(0) == "ok" and "unknown" in lib.status_string(99)
+    assert lib.page_stats_stride(good_desc()) == 8 * 128 + 32 and lib.c.unique_page_stats_stride(None) == 0
 
 
 def test_workspace_bytes(lib):
     n = lib.workspace_bytes(good_desc(), 16)
     assert n > 0 and n % 256 == 0
     # needs dimensions only
-    assert lib.workspace_bytes(good_desc(k_cache=0, v_cache=0, page_mean=0, page_std=0, page_table=0, seq_lens=0), 16) == n
+    assert lib.workspace_bytes(good_desc(k_cache=0, v_cache=0, page_stats=0, page_table=0, seq_lens=0), 16) == n
     # grows with the batch, covers score rows
     assert lib.workspace_bytes(good_desc(batch=64), 16) > n
     big = lib.workspace_bytes(good_desc(batch=1, max_pages_per_seq=16384), 256)
@@ -59,6 +60,7 @@ def test_workspace_bytes(lib):
     (dict(page_size=12), binding.ERR_UNSUPPORTED),
     (dict(num_q_heads=24, num_kv_heads=8), binding.ERR_UNSUPPORTED),   # G = 3
     (dict(num_q_heads=12, num_kv_heads=12), binding.ERR_UNSUPPORTED),  # Hkv = 12
+    (dict(num_q_heads=64, num_kv_heads=64), binding.ERR_UNSUPPORTED),  # Hkv = 64
     (dict(k_cache=0), binding.ERR_INVALID_ARG),
     (dict(page_table=0), binding.ERR_INVALID_ARG),
     (dict(k_cache=0x1004), binding.ERR_INVALID_ARG),          # misaligned
@@ -78,7 +80,7 @@ def test_call_argument_validation(lib):
     c = lib.c
     # stats
     assert c.unique_update_page_stats(None, None, None, 0, None) == binding.ERR_INVALID_ARG
-    assert c.unique_update_page_stats(C.byref(good_desc(page_mean=0)), None, None, 0, None) == binding.ERR_INVALID_ARG
+    assert c.unique_update_page_stats(C.byref(good_desc(page_stats=0)), None, None, 0, None) == binding.ERR_INVALID_ARG
     assert c.unique_update_page_stats(C.byref(d), 0x100, None, 1, None) == binding.ERR_INVALID_ARG
     assert c.unique_update_page_stats(C.byref(d), 0x100, 0x200, -1, None) == binding.ERR_INVALID_ARG
     # score + select
@@ -92,7 +94,7 @@ def test_call_argument_validation(lib):
     assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, 16, None) == binding.ERR_WORKSPACE
     assert "too small" in lib.last_error()
     assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, ws + 8, nws, None) == binding.ERR_WORKSPACE
-    assert f(C.byref(good_desc(page_std=0)), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert f(C.byref(good_desc(page_stats=0)), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
     # sparse decode
     g = c.unique_sparse_paged_decode
     assert g(C.byref(d), 0x7000, None, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG

@@ -72,6 +72,8 @@ def test_config4_reduced_with_appends(gpu_lib):
     for b in range(wl.B):
         used[wl.page_table[b, :wl.num_pages(b)].long()] = True
     assert torch.equal(inc_mean[used], sess.page_mean[used]) and torch.equal(inc_std[used], sess.page_std[used])
+    # pad floats of the records and records of unused pages are never written
+    assert torch.isnan(sess.page_stats[:, wl.Hkv * wl.D + wl.Hkv:]).all() and torch.isnan(sess.page_stats[~used]).all()
 
 
 @pytest.mark.parametrize("top_k", [64, 256, 1024])
@@ -117,6 +119,67 @@ def test_exact_ties_take_lowest_pages(gpu_lib):
     wl2.k_cache[1::2] = wl2.k_cache[0::2].clone()  # page 2i+1 duplicates page 2i
     _, rep2 = Hn.full_check(wl2.to(DEV))
     assert rep2["exact_sets"] == rep2["rows"]
+
+
+def _crafted_select(P, top_k, make_scores, S=8):
+    """Plant arbitrary fp32 scores: q = e_0 and mean[.., 0] = score, std = 0, so Eq. 3 returns them exactly."""
+    wl = W.build("crafted", 9, dtype=torch.float32, B=2, H=2, Hkv=2, D=64, S=S, seq_lens=[P * S, P * S - 3],
+                 top_k=top_k, key_mode="iid", poison=False).to(DEV)
+    wl.q.zero_()
+    wl.q[..., 0] = 1.0
+    sess = DecodeSession(wl)
+    sess.page_stats.zero_()
+    rows = {}
+    for b in range(2):
+        for h in range(2):
+            sc = make_scores(P, 10 * b + h).astype(np.float32)
+            rows[(b, h)] = sc
+            sess.page_mean[wl.page_table[b, :P].long(), h, 0] = torch.from_numpy(sc).to(DEV)
+    sess.score_select_topk()
+    torch.cuda.synchronize()
+    sel, cnt, got = sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sess.scores.cpu().numpy()
+    for (b, h), sc in rows.items():
+        assert np.array_equal(got[b, h, :P], sc, equal_nan=True), "planted scores did not come back exactly"
+        kb = min(top_k, P)
+        nan = np.isnan(sc)
+        key = np.where(nan, -np.inf, sc.astype(np.float64))
+        order = np.lexsort((np.arange(P), -key, nan))      # NaN last, then score descending, then page ascending
+        expect = np.sort(order[:kb])
+        assert cnt[b, h] == kb
+        assert np.array_equal(sel[b, h, :kb], expect), f"P={P} k={top_k} row ({b},{h})"
+        assert (sel[b, h, kb:] == -1).all()
+        if not nan.any():                                   # the oracle's ranking agrees with numpy's
+            o, _ = oracle.topk(sc.astype(np.float64), top_k)
+            assert np.array_equal(np.sort(o[:kb]), expect)
+
+
+SCORE_MAKERS = {
+    "normal": lambda P, s: np.random.default_rng(s).normal(size=P) * 8,
+    "heavy_ties": lambda P, s: np.round(np.random.default_rng(s).normal(size=P), 1),
+    "all_equal": lambda P, s: np.full(P, -2.5),
+    "two_values": lambda P, s: np.where(np.random.default_rng(s).random(P) < 0.5, 1.0, 2.0),
+    "signed_zeros": lambda P, s: np.where(np.arange(P) % 3 == 0, -0.0, np.where(np.arange(P) % 3 == 1, 0.0, -1.0)),
+    "huge_range": lambda P, s: np.random.default_rng(s).choice([1e30, -1e30, 1.0, 1e-30, -3e38, 3e38], size=P),
+    "denormal": lambda P, s: np.random.default_rng(s).integers(-50, 50, size=P) * 1e-42,
+    "ascending": lambda P, s: np.arange(P, dtype=np.float64),
+    "descending": lambda P, s: -np.arange(P, dtype=np.float64),
+    "nan_and_inf": lambda P, s: np.where(np.arange(P) % 7 == 0, np.nan, np.where(
+        np.arange(P) % 11 == 0, np.inf, np.where(np.arange(P) % 13 == 0, -np.inf,
+                                                  np.random.default_rng(s).normal(size=P)))),
+    "one_outlier": lambda P, s: np.where(np.arange(P) == P // 2, 1e6, np.random.default_rng(s).normal(size=P) * 1e-3),
+}
+
+
+@pytest.mark.parametrize("kind", sorted(SCORE_MAKERS))
+@pytest.mark.parametrize("P,top_k", [(200, 16), (3000, 64), (8192, 256), (20000, 1024)])
+def test_select_exact_on_crafted_scores(gpu_lib, kind, P, top_k):
+    _crafted_select(P, top_k, SCORE_MAKERS[kind])
+
+
+@pytest.mark.parametrize("P", [255, 256, 257, 1024, 1025, 2048, 2049, 4096, 4097, 8193, 16384, 16385, 32768, 33000])
+def test_select_row_length_boundaries(gpu_lib, P):
+    _crafted_select(P, 37, SCORE_MAKERS["heavy_ties"])
+    _crafted_select(P, P - 1, SCORE_MAKERS["normal"])
 
 
 def test_select_all_pages_equals_dense(gpu_lib):
