@@ -119,21 +119,27 @@ def main():
     ms_per_step = start.elapsed_time(stop) / args.steps
 
     # --- the same K steps again with an event between stages (stage breakdown; the events cost a little)
-    marks = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    # (score and select are launched through their own entry points here: the same two kernels as the fused call)
+    stride = (wl.max_pages + 63) // 64 * 64
+    score_buf = torch.empty((wl.B, wl.Hkv, stride), device=dev, dtype=torch.float32)
+    marks = [[ev() for _ in range(5)] for _ in range(args.steps)]
     for i in range(args.steps):
         marks[i][0].record()
         sess.update_page_stats(tok_begin, tok_end, 1)
         marks[i][1].record()
-        sess.score_select_topk()
+        sess.page_scores(score_buf)
         marks[i][2].record()
-        sess.sparse_paged_decode()
+        sess.select_topk(score_buf)
         marks[i][3].record()
+        sess.sparse_paged_decode()
+        marks[i][4].record()
     torch.cuda.synchronize()
     import statistics as st
     def stage(j):
         xs = sorted(marks[i][j].elapsed_time(marks[i][j + 1]) * 1e3 for i in range(args.steps))
         return {"mean": st.fmean(xs), "median": xs[len(xs) // 2], "p10": xs[len(xs) // 10], "p90": xs[(9 * len(xs)) // 10]}
-    stages = {"update_page_stats_tail": stage(0), "score_select_topk": stage(1), "sparse_paged_decode": stage(2)}
+    stages = {"update_page_stats_tail": stage(0), "page_scores": stage(1), "select_topk": stage(2),
+              "sparse_paged_decode": stage(3)}
 
     # --- per-kernel durations inside the calls (score vs select, partial vs merge): timed one kernel pair at a time
     def timed(fn, n):
@@ -155,21 +161,22 @@ def main():
     sel_count = sess.sel_count.cpu()
     ab = algorithmic_bytes(wl, sess, sel_count, seq_lens)
 
-    # dominant kernel of the step: whichever call takes longest, priced on its algorithmic bytes.
-    # The select and merge kernels are small next to the score and partial kernels of the same calls, so the
-    # call durations bound the kernel durations from above (achieved GB/s is therefore slightly understated).
-    score_us = stages["score_select_topk"]["mean"]
-    dec_us = stages["sparse_paged_decode"]["mean"]
+    # dominant kernel of the step: whichever takes longest, priced on its algorithmic bytes. The page-score,
+    # select and stats calls are one kernel each; the decode call is the split-K partial kernel plus the small
+    # merge kernel, so its duration bounds the partial kernel's from above (its GB/s is slightly understated).
     by_kernel = {
-        "page_score_kernel(+select)": {"bytes": ab["page_score_kernel"] + ab["topk_select_kernel"], "us": score_us},
-        "paged_decode_partial_kernel(+merge)": {"bytes": ab["paged_decode_partial_kernel"], "us": dec_us},
+        "page_stats_kernel(tail)": {"bytes": ab["page_stats_kernel"], "us": stages["update_page_stats_tail"]["mean"]},
+        "page_score_kernel": {"bytes": ab["page_score_kernel"], "us": stages["page_scores"]["mean"]},
+        "topk_select_kernel": {"bytes": ab["topk_select_kernel"], "us": stages["select_topk"]["mean"]},
+        "paged_decode_partial_kernel(+merge)": {"bytes": ab["paged_decode_partial_kernel"],
+                                                "us": stages["sparse_paged_decode"]["mean"]},
     }
     for v in by_kernel.values():
         v["GBps"] = v["bytes"] / v["us"] / 1e3
         v["frac"] = v["GBps"] / HBM_PEAK_GBPS
     dom = max(by_kernel, key=lambda k: by_kernel[k]["us"])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": by_kernel[dom]["GBps"], "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": by_kernel[dom]["frac"], "traffic": None,
+                "unit": "GB/s", "frac": by_kernel[dom]["frac"], "traffic": measured_traffic(wl.name, dom),
                 "algorithmic_bytes_per_launch": by_kernel[dom]["bytes"], "avg_launch_us": by_kernel[dom]["us"],
                 "by_kernel": by_kernel}
     if dense_us is not None:
@@ -200,6 +207,18 @@ def main():
         "paper_context": "paper: 11.4x attention-path speedup over dense FlashInfer at 32K, >=5.3x end to end (1x H100, S=8, batch 80)",
     }
     print(json.dumps(line))
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if any."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel.split("(")[0]:
+            return float(parts[2])
+    return None
 
 
 def cpu_baseline(wl, sess):

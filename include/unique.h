@@ -115,6 +115,18 @@ int unique_score_select_topk(const unique_cache_desc* desc, const void* d_q, int
                              int32_t* d_sel_pages, int32_t* d_sel_count, float* d_scores_out,
                              void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* The two halves of unique_score_select_topk as separate calls (same kernels), for callers that keep
+ * the score rows or bring their own.
+ * unique_page_scores: Eq. 6 scores only. d_scores : out, float, row (b, h_kv) at
+ *   d_scores + (b*H_kv + h_kv)*score_stride, entries [0, pages of the sequence) written;
+ *   score_stride >= max_pages_per_seq (or the page bound implied by max_seq_len_hint) and a multiple of 4;
+ *   d_scores 16-byte aligned.
+ * unique_select_topk: top-k page set of each row of d_scores (same layout), outputs as above. */
+int unique_page_scores(const unique_cache_desc* desc, const void* d_q, float lambda, float* d_scores,
+                       int32_t score_stride, void* stream);
+int unique_select_topk(const unique_cache_desc* desc, const float* d_scores, int32_t score_stride, int32_t top_k,
+                       int32_t* d_sel_pages, int32_t* d_sel_count, void* stream);
+
 /* Sparse paged decode attention, Eq. 5: for each query head, softmax(q K_T^T * sm_scale) V_T over
  * the valid tokens of the selected pages T of its KV head.
  *   d_sel_pages : int32, row (b, h_kv) starts at d_sel_pages + (b*H_kv + h_kv)*sel_stride and holds

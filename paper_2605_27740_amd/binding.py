@@ -18,7 +18,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 DTYPE_CODE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = ("unique_workspace_bytes", "unique_page_stats_stride", "unique_update_page_stats", "unique_score_select_topk",
-           "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
+           "unique_page_scores", "unique_select_topk", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
            "unique_last_error", "unique_version")
 
 
@@ -61,6 +61,10 @@ class Library:
         self.c.unique_score_select_topk.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_float,
                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                                     C.c_void_p]
+        self.c.unique_page_scores.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_float, C.c_void_p, C.c_int32,
+                                              C.c_void_p]
+        self.c.unique_select_topk.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
         self.c.unique_sparse_paged_decode.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                                       C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                                       C.c_size_t, C.c_void_p]
@@ -99,6 +103,13 @@ class Library:
         self.check(self.c.unique_score_select_topk(C.byref(desc), _p(q), top_k, lam, _p(sel_pages), _p(sel_count),
                                                    _p(scores_out), _p(workspace),
                                                    workspace.numel() * workspace.element_size(), _stream()))
+
+    def page_scores(self, desc: CacheDesc, q, lam: float, scores):
+        self.check(self.c.unique_page_scores(C.byref(desc), _p(q), lam, _p(scores), int(scores.shape[-1]), _stream()))
+
+    def select_topk(self, desc: CacheDesc, scores, top_k: int, sel_pages, sel_count):
+        self.check(self.c.unique_select_topk(C.byref(desc), _p(scores), int(scores.shape[-1]), top_k, _p(sel_pages),
+                                             _p(sel_count), _stream()))
 
     def sparse_paged_decode(self, desc: CacheDesc, q, sel_pages, sel_count, sel_stride: int, sm_scale: float, out,
                             lse_out, workspace):

@@ -168,6 +168,39 @@ int unique_score_select_topk(const unique_cache_desc* desc, const void* d_q, int
   return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "top-k select launch");
 }
 
+int unique_page_scores(const unique_cache_desc* desc, const void* d_q, float lambda, float* d_scores,
+                       int32_t score_stride, void* stream) {
+  unique::CacheView v;
+  const int rc = make_view(desc, &v, true, false);
+  if (rc != UNIQUE_OK) return rc;
+  if (!d_q || !d_scores) return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_scores must be non-NULL");
+  if (((uintptr_t)d_q | (uintptr_t)d_scores) & 15u)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_scores must be 16-byte aligned");
+  if (!(lambda >= 0.f)) return fail(UNIQUE_ERR_INVALID_ARG, "lambda must be >= 0");
+  if (score_stride < v.max_pages_hint || score_stride % 4 != 0)
+    return fail(UNIQUE_ERR_INVALID_ARG, "score_stride %d must be a multiple of 4 and >= %d pages", score_stride,
+                v.max_pages_hint);
+  const hipError_t e = unique::launch_score(v, d_q, lambda, d_scores, score_stride, nullptr, (hipStream_t)stream);
+  return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "page score launch");
+}
+
+int unique_select_topk(const unique_cache_desc* desc, const float* d_scores, int32_t score_stride, int32_t top_k,
+                       int32_t* d_sel_pages, int32_t* d_sel_count, void* stream) {
+  unique::CacheView v;
+  const int rc = make_view(desc, &v, false, false);
+  if (rc != UNIQUE_OK) return rc;
+  if (!d_scores || !d_sel_pages || !d_sel_count)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_scores, d_sel_pages and d_sel_count must be non-NULL");
+  if ((uintptr_t)d_scores & 15u) return fail(UNIQUE_ERR_INVALID_ARG, "d_scores must be 16-byte aligned");
+  if (top_k < 1) return fail(UNIQUE_ERR_INVALID_ARG, "top_k must be >= 1 (got %d)", top_k);
+  if (score_stride < v.max_pages_hint || score_stride % 4 != 0)
+    return fail(UNIQUE_ERR_INVALID_ARG, "score_stride %d must be a multiple of 4 and >= %d pages", score_stride,
+                v.max_pages_hint);
+  const hipError_t e = unique::launch_select(v, d_scores, score_stride, top_k, d_sel_pages, d_sel_count,
+                                             (hipStream_t)stream);
+  return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "top-k select launch");
+}
+
 int unique_sparse_paged_decode(const unique_cache_desc* desc, const void* d_q, const int32_t* d_sel_pages,
                                const int32_t* d_sel_count, int32_t sel_stride, float sm_scale, void* d_out,
                                float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream) {

@@ -50,6 +50,12 @@ class DecodeSession:
         self.lib.score_select_topk(self.desc, self.wl.q, self.top_k, self.wl.lam if lam is None else lam,
                                    self.sel_pages, self.sel_count, self.scores, self.workspace)
 
+    def page_scores(self, scores, lam: float | None = None):
+        self.lib.page_scores(self.desc, self.wl.q, self.wl.lam if lam is None else lam, scores)
+
+    def select_topk(self, scores):
+        self.lib.select_topk(self.desc, scores, self.top_k, self.sel_pages, self.sel_count)
+
     def sparse_paged_decode(self, sm_scale: float = 0.0, sel_pages=None, sel_count=None):
         sel_pages = self.sel_pages if sel_pages is None else sel_pages
         sel_count = self.sel_count if sel_count is None else sel_count

@@ -95,6 +95,15 @@ def test_call_argument_validation(lib):
     assert "too small" in lib.last_error()
     assert f(C.byref(d), 0x7000, 4, 0.5, 0x100, 0x200, None, ws + 8, nws, None) == binding.ERR_WORKSPACE
     assert f(C.byref(good_desc(page_stats=0)), 0x7000, 4, 0.5, 0x100, 0x200, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    # the two halves on their own
+    ps, st = c.unique_page_scores, c.unique_select_topk
+    assert ps(C.byref(d), 0x7000, 0.5, None, 64, None) == binding.ERR_INVALID_ARG
+    assert ps(C.byref(d), 0x7000, 0.5, 0x9000, 60, None) == binding.ERR_INVALID_ARG     # stride < pages
+    assert ps(C.byref(d), 0x7000, 0.5, 0x9000, 66, None) == binding.ERR_INVALID_ARG     # not a multiple of 4
+    assert ps(C.byref(d), 0x7000, 0.5, 0x9004, 64, None) == binding.ERR_INVALID_ARG     # misaligned
+    assert st(C.byref(d), None, 64, 4, 0x100, 0x200, None) == binding.ERR_INVALID_ARG
+    assert st(C.byref(d), 0x9000, 64, 0, 0x100, 0x200, None) == binding.ERR_INVALID_ARG
+    assert st(C.byref(d), 0x9000, 32, 4, 0x100, 0x200, None) == binding.ERR_INVALID_ARG
     # sparse decode
     g = c.unique_sparse_paged_decode
     assert g(C.byref(d), 0x7000, None, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG

@@ -182,6 +182,24 @@ def test_select_row_length_boundaries(gpu_lib, P):
     _crafted_select(P, P - 1, SCORE_MAKERS["normal"])
 
 
+def test_split_score_and_select_calls_match_the_fused_call(gpu_lib):
+    wl = W.config3(batch=2, context=8192 + 7, top_k=48).to(DEV)
+    sess = DecodeSession(wl)
+    sess.update_page_stats()
+    sess.score_select_topk()
+    sel_f, cnt_f, sc_f = sess.sel_pages.clone(), sess.sel_count.clone(), sess.scores.clone()
+    stride = (wl.max_pages + 3) // 4 * 4 + 8
+    buf = torch.full((wl.B, wl.Hkv, stride), float("nan"), device=DEV)
+    sess.page_scores(buf)
+    sess.sel_pages.fill_(-9)
+    sess.sel_count.fill_(-9)
+    sess.select_topk(buf)
+    torch.cuda.synchronize()
+    P = wl.num_pages(0)
+    assert torch.equal(buf[:, :, :P], sc_f[:, :, :P]) and torch.isnan(buf[:, :, P:]).all()
+    assert torch.equal(sess.sel_pages, sel_f) and torch.equal(sess.sel_count, cnt_f)
+
+
 def test_select_all_pages_equals_dense(gpu_lib):
     wl = W.config3(batch=2, context=4096 + 5, top_k=32).to(DEV)
     sess = DecodeSession(wl)
