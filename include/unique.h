@@ -25,11 +25,13 @@
  *
  * Memory layout (row-major, innermost last)
  *   k_cache, v_cache : [num_phys_pages][num_kv_heads][page_size][head_dim]   dtype
- *   page_stats       : [num_phys_pages][num_kv_heads*head_dim + 32]          float
- *                      one record per physical page: the mean vectors of its KV heads
- *                      (head h at floats [h*D, (h+1)*D)), then the scalar stds (head h at float
- *                      num_kv_heads*D + h), padded to 32 floats so that a page's statistics are
- *                      one contiguous, 128-byte-aligned block; pad floats are never read or written
+ *   page_stats       : one record per physical page, unique_page_stats_record_bytes(desc) bytes each:
+ *                      the mean vectors of its KV heads (head h at elements [h*D, (h+1)*D), element type
+ *                      float for stats_dtype fp32, bf16 for stats_dtype bf16), then the scalar stds as
+ *                      float (head h at float index h after the means), padded by a 128-byte block, so
+ *                      that a page's statistics are one contiguous, 128-byte-aligned run:
+ *                      record bytes = num_kv_heads*D*sizeof(mean element) + 128. Pad bytes are never
+ *                      read or written. The base pointer must be 128-byte aligned.
  *   page_table       : [batch][max_pages_per_seq]  int32, logical page -> physical page
  *   seq_lens         : [batch] int32, tokens cached per sequence INCLUDING the token being
  *                      decoded (the caller appends k_t, v_t first); must be >= 1
@@ -74,9 +76,14 @@ typedef struct unique_cache_desc {
   int64_t num_phys_pages;    /* pages in the pool */
   const void* k_cache;       /* device */
   const void* v_cache;       /* device */
-  float* page_stats;         /* device, written by unique_update_page_stats, read by unique_score_select_topk */
+  void* page_stats;          /* device, written by unique_update_page_stats, read by unique_score_select_topk */
   const int32_t* page_table; /* device */
   const int32_t* seq_lens;   /* device */
+  int32_t stats_dtype;       /* UNIQUE_DTYPE_F32: means kept in fp32 (selection equals an exact ranking of
+                                fp32 scores). UNIQUE_DTYPE_BF16: means rounded to bf16 (the paper's storage
+                                format, half the bytes of the score stage); scores and selection are then exact
+                                with respect to the STORED statistics. The std is fp32 in both. */
+  int32_t reserved;          /* must be 0 */
 } unique_cache_desc;
 
 /* Bytes of device workspace that any of the calls below may need for this descriptor and top_k
@@ -84,8 +91,9 @@ typedef struct unique_cache_desc {
  * The contents need no initialisation and carry nothing between calls. */
 int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t* out_bytes);
 
-/* Floats per page record of page_stats for this descriptor (num_kv_heads*head_dim + 32); 0 if desc is NULL. */
-int64_t unique_page_stats_stride(const unique_cache_desc* desc);
+/* Bytes per page record of page_stats for this descriptor (see the layout above); 0 if desc is NULL or
+ * its stats_dtype is not one of the two. */
+int64_t unique_page_stats_record_bytes(const unique_cache_desc* desc);
 
 /* Page statistics, Eq. 1 (mean over the page's keys, per dimension) and Eq. 2 (per-dimension
  * population standard deviation collapsed by its l2 norm into one scalar), recomputed from the

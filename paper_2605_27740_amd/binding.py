@@ -17,7 +17,7 @@ from . import build as _build
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 DTYPE_CODE = {torch.float32: 0, torch.bfloat16: 1}
 
-EXPORTS = ("unique_workspace_bytes", "unique_page_stats_stride", "unique_update_page_stats", "unique_score_select_topk",
+EXPORTS = ("unique_workspace_bytes", "unique_page_stats_record_bytes", "unique_update_page_stats", "unique_score_select_topk",
            "unique_page_scores", "unique_select_topk", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
            "unique_last_error", "unique_version")
 
@@ -28,7 +28,8 @@ class CacheDesc(C.Structure):
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("batch", C.c_int32),
                 ("max_pages_per_seq", C.c_int32), ("max_seq_len_hint", C.c_int32),
                 ("num_phys_pages", C.c_int64), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
-                ("page_stats", C.c_void_p), ("page_table", C.c_void_p), ("seq_lens", C.c_void_p)]
+                ("page_stats", C.c_void_p), ("page_table", C.c_void_p), ("seq_lens", C.c_void_p),
+                ("stats_dtype", C.c_int32), ("reserved", C.c_int32)]
 
 
 class UniqueError(RuntimeError):
@@ -55,8 +56,8 @@ class Library:
             getattr(self.c, name).restype = C.c_char_p
         self.c.unique_status_string.argtypes = [C.c_int]
         self.c.unique_workspace_bytes.argtypes = [C.POINTER(CacheDesc), C.c_int32, C.POINTER(C.c_size_t)]
-        self.c.unique_page_stats_stride.argtypes = [C.POINTER(CacheDesc)]
-        self.c.unique_page_stats_stride.restype = C.c_int64
+        self.c.unique_page_stats_record_bytes.argtypes = [C.POINTER(CacheDesc)]
+        self.c.unique_page_stats_record_bytes.restype = C.c_int64
         self.c.unique_update_page_stats.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         self.c.unique_score_select_topk.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_float,
                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -91,8 +92,8 @@ class Library:
         self.check(self.c.unique_workspace_bytes(C.byref(desc), top_k, C.byref(n)))
         return int(n.value)
 
-    def page_stats_stride(self, desc: CacheDesc) -> int:
-        return int(self.c.unique_page_stats_stride(C.byref(desc)))
+    def page_stats_record_bytes(self, desc: CacheDesc) -> int:
+        return int(self.c.unique_page_stats_record_bytes(C.byref(desc)))
 
     def update_page_stats(self, desc: CacheDesc, tok_begin=None, tok_end=None, max_pages_touched_per_seq: int = 0):
         self.check(self.c.unique_update_page_stats(C.byref(desc), _p(tok_begin), _p(tok_end),
@@ -137,11 +138,15 @@ def load() -> Library:
     return _lib
 
 
-STD_BLOCK = 32  # floats after the means in a page_stats record
+STD_BLOCK_BYTES = 128  # bytes after the means in a page_stats record (fp32 stds + pad)
+
+
+def stats_record_bytes(num_kv_heads: int, head_dim: int, stats_dtype) -> int:
+    return num_kv_heads * head_dim * (2 if stats_dtype == torch.bfloat16 else 4) + STD_BLOCK_BYTES
 
 
 def make_desc(*, q_heads: int, k_cache, v_cache, page_stats, page_table, seq_lens,
-              max_seq_len_hint: int = 0) -> CacheDesc:
+              max_seq_len_hint: int = 0, stats_dtype=torch.float32) -> CacheDesc:
     """Fill a ``unique_cache_desc`` from tensors laid out as include/unique.h describes (shape checks only)."""
     P, Hkv, S, D = k_cache.shape
     assert k_cache.dtype in DTYPE_CODE and k_cache.is_contiguous()
@@ -149,9 +154,9 @@ def make_desc(*, q_heads: int, k_cache, v_cache, page_stats, page_table, seq_len
     assert page_table.dtype == torch.int32 and page_table.is_contiguous() and page_table.dim() == 2
     assert seq_lens.dtype == torch.int32 and seq_lens.shape == (page_table.shape[0],)
     if page_stats is not None:
-        assert page_stats.dtype == torch.float32 and page_stats.is_contiguous()
-        assert page_stats.shape == (P, Hkv * D + STD_BLOCK)
+        assert page_stats.dtype == torch.uint8 and page_stats.is_contiguous()
+        assert page_stats.shape == (P, stats_record_bytes(Hkv, D, stats_dtype))
     return CacheDesc(DTYPE_CODE[k_cache.dtype], q_heads, Hkv, D, S, page_table.shape[0], page_table.shape[1],
                      max_seq_len_hint, P, k_cache.data_ptr(), 0 if v_cache is None else v_cache.data_ptr(),
                      0 if page_stats is None else page_stats.data_ptr(),
-                     page_table.data_ptr(), seq_lens.data_ptr())
+                     page_table.data_ptr(), seq_lens.data_ptr(), DTYPE_CODE[stats_dtype], 0)

@@ -56,8 +56,12 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
     return fail(UNIQUE_ERR_INVALID_ARG, "k_cache, page_table and seq_lens must be non-NULL");
   if (need_v && !d->v_cache) return fail(UNIQUE_ERR_INVALID_ARG, "v_cache is NULL");
   if (need_stats && !d->page_stats) return fail(UNIQUE_ERR_INVALID_ARG, "page_stats must be non-NULL");
-  const uintptr_t misaligned = (uintptr_t)d->k_cache | (uintptr_t)d->v_cache | (uintptr_t)d->page_stats;
-  if (misaligned & 15u) return fail(UNIQUE_ERR_INVALID_ARG, "k_cache, v_cache and page_stats must be 16-byte aligned");
+  const uintptr_t misaligned = (uintptr_t)d->k_cache | (uintptr_t)d->v_cache;
+  if (misaligned & 15u) return fail(UNIQUE_ERR_INVALID_ARG, "k_cache and v_cache must be 16-byte aligned");
+  if ((uintptr_t)d->page_stats & 127u) return fail(UNIQUE_ERR_INVALID_ARG, "page_stats must be 128-byte aligned");
+  if (d->stats_dtype != UNIQUE_DTYPE_F32 && d->stats_dtype != UNIQUE_DTYPE_BF16)
+    return fail(UNIQUE_ERR_INVALID_ARG, "stats_dtype %d is neither fp32 (0) nor bf16 (1)", d->stats_dtype);
+  if (d->reserved != 0) return fail(UNIQUE_ERR_INVALID_ARG, "reserved field must be 0");
 
   v->k_cache = d->k_cache;
   v->v_cache = d->v_cache;
@@ -78,6 +82,9 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
     if (hp < hint_pages) hint_pages = (int)hp;
   }
   v->max_pages_hint = hint_pages;
+  v->stats_bf16 = d->stats_dtype == UNIQUE_DTYPE_BF16;
+  v->rec_bytes = unique_page_stats_record_bytes(d);
+  v->stream_nt = 0;
   return UNIQUE_OK;
 }
 
@@ -127,9 +134,11 @@ int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t*
   return UNIQUE_OK;
 }
 
-int64_t unique_page_stats_stride(const unique_cache_desc* desc) {
+int64_t unique_page_stats_record_bytes(const unique_cache_desc* desc) {
   if (!desc) return 0;
-  return (int64_t)desc->num_kv_heads * desc->head_dim + unique::kStdBlock;
+  if (desc->stats_dtype != UNIQUE_DTYPE_F32 && desc->stats_dtype != UNIQUE_DTYPE_BF16) return 0;
+  const int64_t elem = desc->stats_dtype == UNIQUE_DTYPE_BF16 ? 2 : 4;
+  return (int64_t)desc->num_kv_heads * desc->head_dim * elem + unique::kStdBlockBytes;
 }
 
 int unique_update_page_stats(const unique_cache_desc* desc, const int32_t* d_tok_begin, const int32_t* d_tok_end,

@@ -100,8 +100,8 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
       for (int j = 0; j < kTileLoads; ++j) {
         const int tok = tbase + j * kTokPerLoad + tr;
         if (tok < ntok) {
-          kd[j] = load_raw(kc + page_off + (int64_t)tok * D);
-          vd[j] = load_raw(vc + page_off + (int64_t)tok * D);
+          kd[j] = load_raw_stream(kc + page_off + (int64_t)tok * D, c.stream_nt);
+          vd[j] = load_raw_stream(vc + page_off + (int64_t)tok * D, c.stream_nt);
         } else {
           kd[j] = zero_raw();
           vd[j] = zero_raw();
@@ -212,6 +212,231 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
   }
 }
 
+
+// ---- bf16 caches: the q.k products of a tile of 16 tokens run on the matrix cores ----
+// v_mfma_f32_16x16x32_bf16 computes D[m][n] += sum_k A[m][k] B[k][n] with A rows m = lane % 16, B columns
+// n = lane % 16, each lane supplying 8 consecutive k of its 16-lane group, and the result held as
+// D[4*(lane/16) + i][lane % 16] in register i. With A = the G query heads (rows >= G are zero) and
+// B = the keys of 16 token slots, lanes 0..15 end up with the logits of one token each for heads 0..3
+// (lanes 16..31 for heads 4..7). A lane reads, for MFMA step s, the 16-byte chunk 4*s + lane/16 of
+// its token's key, so the contraction order inside a step is whatever the hardware pairs up -- the
+// same for A and B. Softmax runs on those lanes (one token per lane, tokens reduced across the 16
+// lanes with DPP), the probabilities go through 1 KiB of LDS per wave to the row layout in which V
+// was loaded (a lane owns a 16-byte chunk of a token's value), and the PV products stay on the
+// vector ALUs. This removes the unpack + FMA + lane-reduction work of the q.k stage, which made the
+// all-VALU kernel issue-bound (VALU busy 67 % on the dense stream).
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(const Raw16& r) {
+  return __builtin_bit_cast(bf16x8_t, r.v);
+}
+
+template <int D, int S, int G>
+__global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_kernel(
+    CacheView c, const bf16_t* __restrict__ q, const int32_t* __restrict__ sel_pages,
+    const int32_t* __restrict__ sel_count, int sel_stride, int pages_per_split, int num_splits, float scale_log2,
+    float* __restrict__ part_o, float* __restrict__ part_ml) {
+  constexpr int kVec = 8;
+  constexpr int kTile = 16;                          // token slots per MFMA tile
+  constexpr int kSteps = D / 32;                     // MFMA steps (and K loads per lane) per tile
+  constexpr int kLanesPerTok = D / kVec;             // V row layout: lanes covering one value row
+  constexpr int kTokPerLoad = kWave / kLanesPerTok;
+  constexpr int kVLoads = kTile / kTokPerLoad;       // V loads per lane per tile
+  constexpr int kGPad = G < 4 ? 4 : G;               // floats per token slot in the LDS exchange
+  constexpr int kGroups = (G + 3) / 4;               // 16-lane groups that hold real heads
+  static_assert(G <= 8, "at most 8 query heads per KV head");
+
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int row = b * c.Hkv + hkv;
+  const int N = c.seq_lens[b];
+  const int P = min((N + S - 1) / S, c.max_pages_hint);
+  const int cnt = sel_pages ? min(sel_count[row], sel_stride) : P;
+  const int begin = split * pages_per_split;
+  if (begin >= cnt) return;
+  const int end = min(begin + pages_per_split, cnt);
+
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int kt = lane % 16, kg = lane / 16;                       // K / logit layout: token slot, lane group
+  const int vr_ = lane / kLanesPerTok, vc_ = lane % kLanesPerTok;  // V layout: token row inside a load, chunk
+
+  __shared__ float p_lds[kDecWaves][kTile][kGPad];
+  __shared__ float sm_acc[kDecWaves][G][D];
+  __shared__ float sm_m[kDecWaves][G], sm_l[kDecWaves][G];
+
+  // A operand: query head kt (zero rows beyond G), the 8 elements of chunk 4*s + kg
+  bf16x8_t qa[kSteps];
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) {
+    Raw16 r = zero_raw();
+    if (kt < G) r = load_raw(q + ((int64_t)b * c.H + hkv * G + kt) * D + (4 * s + kg) * kVec);
+    qa[s] = as_bf16x8(r);
+  }
+
+  float m[4], l[4];     // softmax state of heads 4*kg + i: m replicated over the 16 lanes, l a per-lane partial sum
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { m[i] = kNegBig; l[i] = 0.f; }
+  float acc[G][kVec];   // this lane's chunk of the output rows, summed over its token rows
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) acc[g][i] = 0.f;
+
+  const bf16_t* kc = reinterpret_cast<const bf16_t*>(c.k_cache);
+  const bf16_t* vc = reinterpret_cast<const bf16_t*>(c.v_cache);
+  const int64_t head_off = (int64_t)hkv * (S * D);
+  const int64_t page_stride = (int64_t)c.Hkv * (S * D);
+
+  for (int e0 = begin + wave; e0 < end; e0 += kDecWaves * kWave) {
+    int my_phys = 0, my_ntok = 0;
+    {
+      const int e = e0 + lane * kDecWaves;
+      if (e < end) {
+        const int lp = sel_pages ? sel_pages[(int64_t)row * sel_stride + e] : e;
+        if (lp >= 0 && lp < P) {
+          const int ph = c.page_table[(int64_t)b * c.max_pages + lp];
+          if (ph >= 0 && (int64_t)ph < c.num_phys) {
+            my_phys = ph;
+            my_ntok = min(S, N - lp * S);
+          }
+        }
+      }
+    }
+    const int n_ent = min(kWave, (end - e0 + kDecWaves - 1) / kDecWaves);
+    const int n_tiles = (n_ent * S + kTile - 1) / kTile;
+
+    // slot gs (counted over the wave's entries) -> entry gs / S, token gs % S. Entries at or beyond n_ent
+    // were never looked up and carry ntok = 0.
+    auto slot_info = [&](int gs, int& phys, int& ntok, int& tok) {
+      const int ent = gs / S;
+      tok = gs % S;
+      if constexpr (S >= kTile) {  // one entry per tile: uniform, scalar broadcast
+        phys = __builtin_amdgcn_readlane(my_phys, ent);
+        ntok = __builtin_amdgcn_readlane(my_ntok, ent);
+      } else {                     // two pages share a tile: per-lane lookup
+        phys = __shfl(my_phys, ent, kWave);
+        ntok = __shfl(my_ntok, ent, kWave);
+      }
+    };
+
+    Raw16 kr[kSteps], vr[kVLoads], kn[kSteps], vn[kVLoads];
+    bool kvalid_cur = false, kvalid_nxt = false;
+    auto issue = [&](int tile, Raw16(&kd)[kSteps], Raw16(&vd)[kVLoads], bool& kvalid) {
+      int phys, ntok, tok;
+      slot_info(tile * kTile + kt, phys, ntok, tok);
+      kvalid = tok < ntok;
+      const bf16_t* kp = kc + phys * page_stride + head_off + (int64_t)tok * D + kg * kVec;
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) kd[s] = kvalid ? load_raw_stream(kp + s * (4 * kVec), c.stream_nt) : zero_raw();
+#pragma unroll
+      for (int j = 0; j < kVLoads; ++j) {
+        slot_info(tile * kTile + j * kTokPerLoad + vr_, phys, ntok, tok);
+        const bf16_t* vp = vc + phys * page_stride + head_off + (int64_t)tok * D + vc_ * kVec;
+        vd[j] = tok < ntok ? load_raw_stream(vp, c.stream_nt) : zero_raw();
+      }
+    };
+
+    issue(0, kr, vr, kvalid_cur);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      if (tile + 1 < n_tiles) issue(tile + 1, kn, vn, kvalid_nxt);
+
+      f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[s], as_bf16x8(kr[s]), sacc, 0, 0, 0);
+
+      float alpha[4], pr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float sv = kvalid_cur ? sacc[i] * scale_log2 : -INFINITY;
+        const float mx = group_allreduce<16>(sv, OpMax());
+        const float mnew = fmaxf(m[i], mx);
+        alpha[i] = fast_exp2(m[i] - mnew);
+        m[i] = mnew;
+        pr[i] = fast_exp2(sv - mnew);
+        l[i] = fmaf(l[i], alpha[i], pr[i]);
+      }
+      // probabilities of the 16 token slots to LDS, [slot][head]
+      if (kg < kGroups) *reinterpret_cast<float4*>(&p_lds[wave][kt][4 * kg]) = make_float4(pr[0], pr[1], pr[2], pr[3]);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+      // rescale the running output by alpha of each head (held by lane group g / 4, register g % 4)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha[g % 4]), 16 * (g / 4)));
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) acc[g][i] *= a;
+      }
+#pragma unroll
+      for (int j = 0; j < kVLoads; ++j) {
+        float vf[kVec];
+        unpack_bf16x8(vr[j].v, vf);
+        const int ts = j * kTokPerLoad + vr_;
+        float pg[kGPad];
+#pragma unroll
+        for (int g4 = 0; g4 < kGPad; g4 += 4) {
+          const float4 t = *reinterpret_cast<const float4*>(&p_lds[wave][ts][g4]);
+          pg[g4] = t.x; pg[g4 + 1] = t.y; pg[g4 + 2] = t.z; pg[g4 + 3] = t.w;
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int i = 0; i < kVec; ++i) acc[g][i] = fmaf(pg[g], vf[i], acc[g][i]);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) kr[s] = kn[s];
+#pragma unroll
+      for (int j = 0; j < kVLoads; ++j) vr[j] = vn[j];
+      kvalid_cur = kvalid_nxt;
+    }
+  }
+
+  // the wave's result: sum the per-lane l over the 16 token lanes, and acc over the token rows of the V layout
+#pragma unroll
+  for (int i = 0; i < 4; ++i) l[i] = group_allreduce<16>(l[i], OpSum());
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) acc[g][i] = cross_group_allreduce<kLanesPerTok>(acc[g][i], OpSum());
+
+  if (vr_ == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int i = 0; i < kVec; ++i) sm_acc[wave][g][vc_ * kVec + i] = acc[g][i];
+  }
+  if (kt == 0 && kg < kGroups) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (4 * kg + i < G) { sm_m[wave][4 * kg + i] = m[i]; sm_l[wave][4 * kg + i] = l[i]; }
+  }
+  __syncthreads();
+  const int64_t pbase = (int64_t)row * num_splits + split;
+  for (int idx = threadIdx.x; idx < G * D; idx += kDecWaves * kWave) {
+    const int g = idx / D, d = idx % D;
+    float M = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) M = fmaxf(M, sm_m[w][g]);
+    float o = 0.f, L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float sc = fast_exp2(sm_m[w][g] - M);
+      o = fmaf(sm_acc[w][g][d], sc, o);
+      L = fmaf(sm_l[w][g], sc, L);
+    }
+    part_o[(pbase * G + g) * D + d] = o;
+    if (d == 0) {
+      part_ml[(pbase * G + g) * 2 + 0] = M;
+      part_ml[(pbase * G + g) * 2 + 1] = L;
+    }
+  }
+}
+
 // Log-sum-exp merge of the chunk partials of one (sequence, query head); writes out (and lse).
 template <typename T, int D, int G>
 __global__ __launch_bounds__(D) void paged_decode_merge_kernel(CacheView c, const int32_t* __restrict__ sel_count,
@@ -241,16 +466,25 @@ __global__ __launch_bounds__(D) void paged_decode_merge_kernel(CacheView c, cons
 }
 
 template <typename T, int D, int S, int G>
-hipError_t launch_t(const CacheView& c, const void* q, const int32_t* sel, const int32_t* cnt, int sel_stride,
+hipError_t launch_t(const CacheView& cv, const void* q, const int32_t* sel, const int32_t* cnt, int sel_stride,
                     int max_list_len, float sm_scale, void* out, float* lse, float* partials, hipStream_t st) {
+  CacheView c = cv;
   const int rows = c.B * c.Hkv;
+  c.stream_nt = (int64_t)rows * max_list_len * S * D * 2 * (int64_t)sizeof(T) > kStreamNtBytes;
   const SplitPlan plan = plan_splits(rows, max_list_len);
   float* part_o = partials;
   float* part_ml = partials + (size_t)rows * plan.num_splits * G * D;
   const float scale_log2 = (sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)D)) * kLog2e;
-  paged_decode_partial_kernel<T, D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
-      c, reinterpret_cast<const T*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
-      part_o, part_ml);
+#ifndef UNIQUE_DEC_NO_MFMA
+  if constexpr (sizeof(T) == 2)
+    paged_decode_partial_mfma_kernel<D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
+        c, reinterpret_cast<const bf16_t*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
+        part_o, part_ml);
+  else
+#endif
+    paged_decode_partial_kernel<T, D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
+        c, reinterpret_cast<const T*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
+        part_o, part_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   paged_decode_merge_kernel<T, D, G><<<dim3(c.H, c.B), dim3(D), 0, st>>>(
@@ -295,11 +529,16 @@ SplitPlan plan_splits(int rows, int max_list_len) {
 #define UNIQUE_DEC_TARGET_GROUPS 512
 #endif
   constexpr int kTargetGroups = UNIQUE_DEC_TARGET_GROUPS;
+#ifndef UNIQUE_DEC_MAX_PPS
+#define UNIQUE_DEC_MAX_PPS 256
+#endif
   if (rows < 1) rows = 1;
   if (max_list_len < 1) max_list_len = 1;
   const int wanted = (kTargetGroups + rows - 1) / rows;
   int pps = (max_list_len + wanted - 1) / wanted;
   if (pps < 2 * kDecWaves) pps = 2 * kDecWaves;
+  // long lists are cut into many equal chunks so that ragged batches balance across the CUs
+  if (pps > UNIQUE_DEC_MAX_PPS) pps = UNIQUE_DEC_MAX_PPS;
   pps = (pps + kDecWaves - 1) / kDecWaves * kDecWaves;
   SplitPlan p;
   p.pages_per_split = pps;

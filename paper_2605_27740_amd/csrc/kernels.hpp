@@ -9,14 +9,20 @@ namespace unique {
 struct CacheView {
   const void* k_cache;        // [num_phys][Hkv][S][D]
   const void* v_cache;
-  float* page_stats;          // [num_phys][Hkv*D + kStdBlock]: means of all heads, then stds, then pad
+  void* page_stats;           // [num_phys] records: Hkv*D means (fp32 or bf16), Hkv fp32 stds, pad to kStdBlockBytes
   const int32_t* page_table;  // [B][max_pages]
   const int32_t* seq_lens;    // [B]
   int32_t H, Hkv, D, S, B, max_pages;
   int64_t num_phys;
   int32_t dtype;              // 0 fp32, 1 bf16
   int32_t max_pages_hint;     // host bound on pages of any sequence (<= max_pages)
+  int32_t stats_bf16;         // 1: means stored as bf16, 0: fp32
+  int64_t rec_bytes;          // bytes per page record of page_stats
+  int32_t stream_nt;          // set per launch: read the streamed operand with non-temporal loads
 };
+
+// Launches that stream more than this many bytes bypass cache allocation (the Infinity Cache holds 256 MB).
+constexpr int64_t kStreamNtBytes = 96ll << 20;
 
 // How a decode launch is cut into split-K chunks; computed on the host from bounds only.
 struct SplitPlan {
@@ -25,7 +31,7 @@ struct SplitPlan {
 };
 SplitPlan plan_splits(int rows, int max_list_len);
 
-constexpr int kStdBlock = 32;          // floats reserved after the means of a page record (stds + pad)
+constexpr int kStdBlockBytes = 128;     // bytes reserved after the means of a page record (fp32 stds + pad)
 constexpr int kScoreStrideAlign = 64;  // score rows in the workspace are padded to this many floats
 
 bool stats_supported(int dtype, int D, int S);

@@ -3,8 +3,8 @@
 // The G x P intermediate never exists in memory: the G dot products, the rank-one offset and the max
 // over the group are all formed in registers and one float per (KV head, page) is written.
 //
-// Layout of the work: 8 lanes own one (page, KV head) mean row and read it as D/32 16-byte chunks
-// each, so a wave covers 8 consecutive head rows per step -- with 8 KV heads that is exactly one
+// Layout of the work: 8 lanes own one (page, KV head) mean row and read it as 16-byte chunks (D/32
+// of them for fp32 means, D/64 for bf16 means) each, so a wave covers 8 consecutive head rows per step -- with 8 KV heads that is exactly one
 // page record, read as one contiguous block whatever the page table does to page placement, with
 // the page's stds taken from the tail of the same record. Every lane keeps its slices of the G
 // queries of its (fixed) KV head in registers for the whole kernel. The G partial dot products are
@@ -29,21 +29,35 @@ constexpr int kMaxKvHeads = 32;
 constexpr int kRowLanes = 8;                   // lanes per (page, head) row
 constexpr int kRowsPerWave = kWave / kRowLanes;
 
-__device__ __forceinline__ void load_q4(const float* p, float (&out)[4]) { load_vec(p, out); }
-__device__ __forceinline__ void load_q4(const bf16_t* p, float (&out)[4]) {
-  const uint2 v = *reinterpret_cast<const uint2*>(p);
-  out[0] = bits_to_float(v.x << 16); out[1] = bits_to_float(v.x & 0xffff0000u);
-  out[2] = bits_to_float(v.y << 16); out[3] = bits_to_float(v.y & 0xffff0000u);
+// kE consecutive query elements as floats (kE = 4 or 8)
+template <int kE>
+__device__ __forceinline__ void load_q(const float* p, float (&out)[kE]) {
+#pragma unroll
+  for (int i = 0; i < kE; i += 4) {
+    const float4 v = *reinterpret_cast<const float4*>(p + i);
+    out[i] = v.x; out[i + 1] = v.y; out[i + 2] = v.z; out[i + 3] = v.w;
+  }
+}
+template <int kE>
+__device__ __forceinline__ void load_q(const bf16_t* p, float (&out)[kE]) {
+#pragma unroll
+  for (int i = 0; i < kE; i += 4) {
+    const uint2 v = *reinterpret_cast<const uint2*>(p + i);
+    out[i] = bits_to_float(v.x << 16); out[i + 1] = bits_to_float(v.x & 0xffff0000u);
+    out[i + 2] = bits_to_float(v.y << 16); out[i + 3] = bits_to_float(v.y & 0xffff0000u);
+  }
 }
 
-template <typename T, int D, int G>
+// T: element type of q; TS: element type of the stored means (float, or bf16_t for bf16 statistics).
+template <typename T, typename TS, int D, int G>
 __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheView c, const T* __restrict__ q,
                                                                         float lambda, float* __restrict__ scores,
                                                                         int score_stride,
                                                                         float* __restrict__ scores_out) {
-  constexpr int kChunks = D / (4 * kRowLanes);  // 16-byte loads per lane per row
-  constexpr int kUnroll = (G * kChunks > 16) ? (UNIQUE_SCORE_UNROLL / 2 > 0 ? UNIQUE_SCORE_UNROLL / 2 : 1)
-                                             : UNIQUE_SCORE_UNROLL;
+  constexpr int kE = Elem<TS>::kVec;                 // mean elements per 16-byte load
+  constexpr int kChunks = D / (kE * kRowLanes);      // 16-byte loads per lane per row
+  constexpr int kUnroll = (G * kChunks * kE > 64) ? (UNIQUE_SCORE_UNROLL / 2 > 0 ? UNIQUE_SCORE_UNROLL / 2 : 1)
+                                                  : UNIQUE_SCORE_UNROLL;
 
   const int b = blockIdx.y;
   const int N = c.seq_lens[b];
@@ -71,63 +85,64 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     wave_slots = kScoreWaves;
   }
 
-  float qv[G][kChunks][4];
+  float qv[G][kChunks][kE];
   float off[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float qq = 0.f;
 #pragma unroll
     for (int j = 0; j < kChunks; ++j) {
-      load_q4(q + ((int64_t)b * c.H + hkv * G + g) * D + j * (4 * kRowLanes) + cl * 4, qv[g][j]);
+      load_q<kE>(q + ((int64_t)b * c.H + hkv * G + g) * D + j * (kE * kRowLanes) + cl * kE, qv[g][j]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) qq = fmaf(qv[g][j][i], qv[g][j][i], qq);
+      for (int i = 0; i < kE; ++i) qq = fmaf(qv[g][j][i], qv[g][j][i], qq);
     }
     qq = group_allreduce<kRowLanes>(qq, OpSum());
     off[g] = lambda * sqrtf(qq);
   }
 
   const int32_t* pt = c.page_table + (int64_t)b * c.max_pages;
-  const int64_t rec_stride = (int64_t)c.Hkv * D + kStdBlock;
+  const char* stats = reinterpret_cast<const char*>(c.page_stats);
+  const int64_t std_off = (int64_t)c.Hkv * D * (int64_t)sizeof(TS);  // byte offset of the stds inside a record
   const int step_pages = wave_slots * pages_per_step;  // pages the workgroup advances per step
   __shared__ float tile_scores[kMaxKvHeads][kTilePages];
 
   for (int base = tile0 + wave_slot * pages_per_step; base < tile_end; base += step_pages * kUnroll) {
-    const float* rec[kUnroll];
+    const char* rec[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int p = base + u * step_pages + page_in_step;
       int64_t phys = -1;
       if (p < tile_end) phys = pt[p];
-      rec[u] = (phys >= 0 && phys < c.num_phys) ? c.page_stats + phys * rec_stride : nullptr;
+      rec[u] = (phys >= 0 && phys < c.num_phys) ? stats + phys * c.rec_bytes : nullptr;
     }
-    float4 m[kUnroll][kChunks];
+    Raw16 m[kUnroll][kChunks];
     float sd[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       if (rec[u]) {
+        const TS* row = reinterpret_cast<const TS*>(rec[u]) + hkv * D + cl * kE;
 #pragma unroll
-        for (int j = 0; j < kChunks; ++j)
-          m[u][j] = *reinterpret_cast<const float4*>(rec[u] + hkv * D + j * (4 * kRowLanes) + cl * 4);
-        sd[u] = rec[u][c.Hkv * D + hkv];
+        for (int j = 0; j < kChunks; ++j) m[u][j] = load_raw_stream(row + j * (kE * kRowLanes), c.stream_nt);
+        sd[u] = reinterpret_cast<const float*>(rec[u] + std_off)[hkv];
       } else {
 #pragma unroll
-        for (int j = 0; j < kChunks; ++j) m[u][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < kChunks; ++j) m[u][j] = zero_raw();
         sd[u] = 0.f;
       }
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
+      float mf[kChunks][kE];
+#pragma unroll
+      for (int j = 0; j < kChunks; ++j) unpack_raw(m[u][j], mf[j], (const TS*)nullptr);
       float best = 0.f;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float dot = 0.f;
 #pragma unroll
-        for (int j = 0; j < kChunks; ++j) {
-          dot = fmaf(qv[g][j][0], m[u][j].x, dot);
-          dot = fmaf(qv[g][j][1], m[u][j].y, dot);
-          dot = fmaf(qv[g][j][2], m[u][j].z, dot);
-          dot = fmaf(qv[g][j][3], m[u][j].w, dot);
-        }
+        for (int j = 0; j < kChunks; ++j)
+#pragma unroll
+          for (int i = 0; i < kE; ++i) dot = fmaf(qv[g][j][i], mf[j][i], dot);
         dot = group_allreduce<kRowLanes>(dot, OpSum());
         const float s = fmaf(off[g], sd[u], dot);
         best = (g == 0) ? s : fmaxf(best, s);
@@ -151,10 +166,17 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
 }
 
 template <typename T, int D, int G>
-hipError_t launch_t(const CacheView& c, const void* q, float lambda, float* scores, int stride, float* out,
+hipError_t launch_t(const CacheView& cv, const void* q, float lambda, float* scores, int stride, float* out,
                     hipStream_t st) {
+  CacheView c = cv;
+  c.stream_nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
   dim3 grid((c.max_pages_hint + kTilePages - 1) / kTilePages, c.B), block(kScoreWaves * kWave);
-  page_score_kernel<T, D, G><<<grid, block, 0, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores, stride, out);
+  if (c.stats_bf16)
+    page_score_kernel<T, bf16_t, D, G><<<grid, block, 0, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
+                                                               stride, out);
+  else
+    page_score_kernel<T, float, D, G><<<grid, block, 0, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
+                                                              stride, out);
   return hipGetLastError();
 }
 

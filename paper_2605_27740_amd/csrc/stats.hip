@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
   for (int j = 0; j < kLoads; ++j) {
     const int tok = j * kTokPerLoad + tr;
     if (tok < n) {
-      load_vec(base + (int64_t)tok * D, x[j]);
+      unpack_raw(load_raw_stream(base + (int64_t)tok * D, c.stream_nt), x[j], (const T*)nullptr);
 #pragma unroll
       for (int i = 0; i < kVec; ++i) sum[i] += x[j][i];
     } else {
@@ -83,19 +83,34 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
   }
   ss = group_allreduce<kWave>(ss, OpSum());
 
-  float* rec = c.page_stats + phys * ((int64_t)c.Hkv * D + kStdBlock);  // this page's record
+  char* rec = reinterpret_cast<char*>(c.page_stats) + phys * c.rec_bytes;  // this page's record
   if (tr == 0) {
-    float* m = rec + hkv * D + ch * kVec;
+    if (c.stats_bf16) {  // means rounded to bf16 (nearest even); the std above is about the unrounded mean
+      bf16_t* m = reinterpret_cast<bf16_t*>(rec) + hkv * D + ch * kVec;
+      uint32_t w[kVec / 2];
 #pragma unroll
-    for (int i = 0; i < kVec; i += 4)
-      *reinterpret_cast<float4*>(m + i) = make_float4(mean[i], mean[i + 1], mean[i + 2], mean[i + 3]);
+      for (int i = 0; i < kVec; i += 2)
+        w[i / 2] = (uint32_t)float_to_bf16(mean[i]) | ((uint32_t)float_to_bf16(mean[i + 1]) << 16);
+      if constexpr (kVec == 8) *reinterpret_cast<uint4*>(m) = make_uint4(w[0], w[1], w[2], w[3]);
+      else *reinterpret_cast<uint2*>(m) = make_uint2(w[0], w[1]);
+    } else {
+      float* m = reinterpret_cast<float*>(rec) + hkv * D + ch * kVec;
+#pragma unroll
+      for (int i = 0; i < kVec; i += 4)
+        *reinterpret_cast<float4*>(m + i) = make_float4(mean[i], mean[i + 1], mean[i + 2], mean[i + 3]);
+    }
   }
-  if (lane == 0) rec[c.Hkv * D + hkv] = sqrtf(ss * inv_n);
+  if (lane == 0) {
+    const int64_t mean_bytes = (int64_t)c.Hkv * D * (c.stats_bf16 ? 2 : 4);
+    reinterpret_cast<float*>(rec + mean_bytes)[hkv] = sqrtf(ss * inv_n);
+  }
 }
 
 template <typename T, int D>
-hipError_t dispatch_s(const CacheView& c, const int32_t* tb, const int32_t* te, int pages_per_seq, hipStream_t st) {
+hipError_t dispatch_s(const CacheView& cv, const int32_t* tb, const int32_t* te, int pages_per_seq, hipStream_t st) {
+  CacheView c = cv;
   const int items = pages_per_seq * c.Hkv;
+  c.stream_nt = (int64_t)c.B * items * c.S * D * (int64_t)sizeof(T) > kStreamNtBytes;
   dim3 grid((items + kStatsWaves - 1) / kStatsWaves, c.B), block(kStatsWaves * kWave);
   switch (c.S) {
     case 8: page_stats_kernel<T, D, 8><<<grid, block, 0, st>>>(c, tb, te, pages_per_seq); break;

@@ -11,22 +11,26 @@ from .workloads import Workload
 
 class DecodeSession:
     def __init__(self, wl: Workload, top_k: int | None = None, max_seq_len_hint: int | None = None,
-                 want_scores: bool = True, lib: binding.Library | None = None):
+                 want_scores: bool = True, lib: binding.Library | None = None, stats_dtype=torch.float32):
         assert wl.k_cache.is_cuda, "the workload must live on the GPU"
         self.lib = lib or binding.load()
         self.wl = wl
         self.top_k = int(top_k if top_k is not None else wl.top_k)
         dev = wl.k_cache.device
         P = wl.num_phys_pages
-        self.page_stats = torch.full((P, wl.Hkv * wl.D + binding.STD_BLOCK), float("nan"), device=dev,
-                                     dtype=torch.float32)
-        # views into the records: means [P, Hkv, D] and stds [P, Hkv]
-        self.page_mean = self.page_stats[:, :wl.Hkv * wl.D].view(P, wl.Hkv, wl.D)
-        self.page_std = self.page_stats[:, wl.Hkv * wl.D:wl.Hkv * wl.D + wl.Hkv]
+        self.stats_dtype = stats_dtype
+        rec = binding.stats_record_bytes(wl.Hkv, wl.D, stats_dtype)
+        mean_bytes = rec - binding.STD_BLOCK_BYTES
+        # one record per physical page, every byte 0xFF (NaN in fp32 and in bf16) until a kernel writes it
+        self.page_stats = torch.full((P, rec), 0xFF, device=dev, dtype=torch.uint8)
+        # views into the records: means [P, Hkv, D] (fp32 or bf16) and stds [P, Hkv] (fp32)
+        self.page_mean = self.page_stats[:, :mean_bytes].view(stats_dtype).view(P, wl.Hkv, wl.D)
+        self.page_std = self.page_stats[:, mean_bytes:mean_bytes + 4 * wl.Hkv].view(torch.float32)
+        self.page_pad = self.page_stats[:, mean_bytes + 4 * wl.Hkv:]
         if max_seq_len_hint is None:
             max_seq_len_hint = int(wl.seq_lens.max().item()) + int(wl.meta.get("spare_tokens", 0))
         self.desc = binding.make_desc(q_heads=wl.H, k_cache=wl.k_cache, v_cache=wl.v_cache,
-                                      page_stats=self.page_stats,
+                                      page_stats=self.page_stats, stats_dtype=stats_dtype,
                                       page_table=wl.page_table, seq_lens=wl.seq_lens,
                                       max_seq_len_hint=max_seq_len_hint)
         self.sel_pages = torch.full((wl.B, wl.Hkv, self.top_k), -7, device=dev, dtype=torch.int32)
@@ -37,7 +41,7 @@ class DecodeSession:
         self.lse = torch.zeros((wl.B, wl.H), device=dev, dtype=torch.float32)
         self.out_dense = torch.zeros_like(self.out)
         self.lse_dense = torch.zeros_like(self.lse)
-        assert self.lib.page_stats_stride(self.desc) == self.page_stats.shape[1]
+        assert self.lib.page_stats_record_bytes(self.desc) == self.page_stats.shape[1]
         self.workspace_bytes = self.lib.workspace_bytes(self.desc, self.top_k)
         self.workspace = torch.empty((max(self.workspace_bytes, 256),), device=dev, dtype=torch.uint8)
         assert self.workspace.data_ptr() % 256 == 0

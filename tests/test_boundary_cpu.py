@@ -21,7 +21,7 @@ def good_desc(**over):
     # pointers only need to be non-NULL and aligned for validation; nothing dereferences them on the host
     d = dict(dtype=1, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, batch=2,
              max_pages_per_seq=64, max_seq_len_hint=0, num_phys_pages=128, k_cache=0x1000, v_cache=0x2000,
-             page_stats=0x3000, page_table=0x5000, seq_lens=0x6000)
+             page_stats=0x3000, page_table=0x5000, seq_lens=0x6000, stats_dtype=0, reserved=0)
     d.update(over)
     return CacheDesc(**d)
 
@@ -34,7 +34,9 @@ def test_exports_match_header(lib):
         assert hasattr(lib.c, name)
     assert lib.version().startswith("unique-gfx950")
     assert lib.status_string(0) == "ok" and "unknown" in lib.status_string(99)
-    assert lib.page_stats_stride(good_desc()) == 8 * 128 + 32 and lib.c.unique_page_stats_stride(None) == 0
+    assert lib.page_stats_record_bytes(good_desc()) == 8 * 128 * 4 + 128
+    assert lib.page_stats_record_bytes(good_desc(stats_dtype=1)) == 8 * 128 * 2 + 128
+    assert lib.c.unique_page_stats_record_bytes(None) == 0 and lib.page_stats_record_bytes(good_desc(stats_dtype=5)) == 0
 
 
 def test_workspace_bytes(lib):
@@ -65,6 +67,9 @@ def test_workspace_bytes(lib):
     (dict(page_table=0), binding.ERR_INVALID_ARG),
     (dict(k_cache=0x1004), binding.ERR_INVALID_ARG),          # misaligned
     (dict(max_seq_len_hint=-1), binding.ERR_INVALID_ARG),
+    (dict(stats_dtype=3), binding.ERR_INVALID_ARG),
+    (dict(reserved=1), binding.ERR_INVALID_ARG),
+    (dict(page_stats=0x3010), binding.ERR_INVALID_ARG),       # needs 128-byte alignment
 ])
 def test_descriptor_validation(lib, over, code):
     rc = lib.c.unique_dense_paged_decode(C.byref(good_desc(**over)), 0x7000, 0.0, 0x8000, None, 0x10000, 1 << 30, None)

@@ -73,7 +73,7 @@ def test_config4_reduced_with_appends(gpu_lib):
         used[wl.page_table[b, :wl.num_pages(b)].long()] = True
     assert torch.equal(inc_mean[used], sess.page_mean[used]) and torch.equal(inc_std[used], sess.page_std[used])
     # pad floats of the records and records of unused pages are never written
-    assert torch.isnan(sess.page_stats[:, wl.Hkv * wl.D + wl.Hkv:]).all() and torch.isnan(sess.page_stats[~used]).all()
+    assert (sess.page_pad == 0xFF).all() and (sess.page_stats[~used] == 0xFF).all()
 
 
 @pytest.mark.parametrize("top_k", [64, 256, 1024])
@@ -84,13 +84,74 @@ def test_config5_reduced_near_ties(gpu_lib, top_k):
     say(rep)
 
 
+# ------------------------------------------------------------------ bf16 statistic storage (the paper's format)
+
+def test_bf16_stats_config2_all_rows(gpu_lib):
+    say("config2 with bf16 statistic storage")
+    wl = W.config2().to(DEV)
+    sess, rep = Hn.full_check(wl, dense_heads=[(0, 3)], stats_dtype=torch.bfloat16)
+    say(rep)
+    # informational: overlap with the selection from exact statistics
+    ref = DecodeSession(wl)
+    ref.update_page_stats()
+    ref.score_select_topk()
+    torch.cuda.synchronize()
+    same = sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(sess.sel_pages[0].cpu(), ref.sel_pages[0].cpu()))
+    say(f"bf16-stat selection keeps {same} of {wl.Hkv * wl.top_k} pages of the fp32-stat selection")
+    assert same >= 0.9 * wl.Hkv * wl.top_k
+
+
+def test_bf16_stats_config4_reduced_with_appends(gpu_lib):
+    wl = W.config4(batch=5, min_context=200, max_context=5000, top_k=8, spare_tokens=64).to(DEV)
+    sess = DecodeSession(wl, stats_dtype=torch.bfloat16)
+    sess.update_page_stats()
+    for step in range(35):
+        begin = wl.seq_lens.clone()
+        W.append_tokens(wl, step)
+        sess.update_page_stats(begin, wl.seq_lens.clone(), 1)
+        sess.sparse_step()
+    _, rep = Hn.full_check(wl, sess=sess, run_stats=False, dense_heads=[(2, 9)])
+    say(rep)
+    inc = sess.page_stats.clone()
+    sess.update_page_stats()
+    torch.cuda.synchronize()
+    assert torch.equal(inc, sess.page_stats)
+
+
+@pytest.mark.parametrize("top_k", [64, 1024])
+def test_bf16_stats_config5_reduced_near_ties(gpu_lib, top_k):
+    wl = W.config5(batch=2, context=32768, top_k=top_k).to(DEV)
+    _, rep = Hn.full_check(wl, dense_heads=[], stats_dtype=torch.bfloat16)
+    say(rep)
+
+
+@pytest.mark.parametrize("dtype,D,S,H,Hkv", [
+    (torch.bfloat16, 128, 16, 32, 8), (torch.bfloat16, 64, 8, 16, 2), (torch.float32, 128, 32, 16, 2),
+    (torch.float32, 64, 16, 32, 32), (torch.bfloat16, 64, 32, 16, 16), (torch.bfloat16, 128, 8, 4, 1),
+])
+def test_bf16_stats_shape_matrix(gpu_lib, dtype, D, S, H, Hkv):
+    lens = [5 * S + 3, 1, S, 37 * S - 1]
+    wl = W.build("shape", 8, dtype=dtype, B=4, H=H, Hkv=Hkv, D=D, S=S, seq_lens=lens, top_k=6,
+                 key_mode="shift", plant_mode="one_percent", permute=True, spare_tokens=S).to(DEV)
+    _, rep = Hn.full_check(wl, stats_dtype=torch.bfloat16)
+    say(rep)
+
+
+def test_bf16_stats_config3_full_size_sampled(gpu_lib):
+    wl = W.config3(device=DEV)
+    rows = _sampled(wl, 3, 5)
+    _, rep = Hn.full_check(wl, rows=rows, dense_heads=[], stats_dtype=torch.bfloat16)
+    say(rep)
+
+
 # ------------------------------------------------------------------ shapes and edge cases
 
 @pytest.mark.parametrize("dtype,D,S,H,Hkv", [
     (torch.bfloat16, 128, 8, 8, 2), (torch.bfloat16, 128, 32, 8, 8), (torch.bfloat16, 64, 8, 16, 2),
     (torch.bfloat16, 64, 16, 16, 16), (torch.bfloat16, 64, 32, 4, 4), (torch.float32, 128, 8, 8, 4),
     (torch.float32, 128, 16, 2, 1), (torch.float32, 128, 32, 16, 2), (torch.float32, 64, 8, 8, 8),
-    (torch.float32, 64, 32, 2, 2), (torch.bfloat16, 128, 16, 16, 8),
+    (torch.float32, 64, 32, 2, 2), (torch.bfloat16, 128, 16, 16, 8), (torch.bfloat16, 64, 16, 32, 32),
+    (torch.bfloat16, 128, 16, 16, 16),
 ])
 def test_shape_matrix(gpu_lib, dtype, D, S, H, Hkv):
     say(f"shape {dtype} D={D} S={S} H={H} Hkv={Hkv}")

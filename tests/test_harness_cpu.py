@@ -1,0 +1,58 @@
+"""The comparison rules of the GPU parity tests, exercised on the CPU with planted mistakes:
+every rule must accept what it should and reject a wrong result."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from tests import harness as Hn
+from tests.test_oracle_pins import make_case
+
+
+def test_selection_rule_accepts_exact_and_band_swaps_only():
+    s = np.array([5.0, 1.0, 4.0, 3.0, 3.0 + 1e-6, 0.5, 2.0])
+    k = 3
+    exact = np.array([0, 2, 4, -1], np.int32)          # 5, 4, 3+1e-6
+    assert Hn.check_selection_row(exact[:k + 1][:4], 3, s, 3) in (True,)
+    # page 3 (score 3.0) is within 1e-4 relative of the k-th score: swapping it in is a legitimate near-tie
+    swapped = np.array([0, 2, 3], np.int32)
+    assert Hn.check_selection_row(swapped, 3, s, 3) is False
+    with pytest.raises(AssertionError):                 # page 6 (score 2.0) is far below the band
+        Hn.check_selection_row(np.array([0, 2, 6], np.int32), 3, s, 3)
+    with pytest.raises(AssertionError):                 # a clearly better page is missing
+        Hn.check_selection_row(np.array([2, 3, 4], np.int32), 3, s, 3)
+    with pytest.raises(AssertionError):                 # duplicates / not ascending
+        Hn.check_selection_row(np.array([0, 2, 2], np.int32), 3, s, 3)
+    with pytest.raises(AssertionError):                 # wrong count
+        Hn.check_selection_row(np.array([0, 2, 4], np.int32), 2, s, 3)
+    with pytest.raises(AssertionError):                 # out of range
+        Hn.check_selection_row(np.array([0, 2, 9], np.int32), 3, s, 3)
+    with pytest.raises(AssertionError):                 # padding must be -1
+        Hn.check_selection_row(np.array([0, 2, 4, 0], np.int32), 3, s, 3)
+    # a clear gap forces the oracle's set exactly
+    s2 = np.array([5.0, 1.0, 4.0, 3.0, 2.0])
+    with pytest.raises(AssertionError):
+        Hn.check_selection_row(np.array([0, 2, 4], np.int32), 3, s2, 3)
+    # k >= P: all pages
+    assert Hn.check_selection_row(np.array([0, 1, 2, 3, 4, -1], np.int32), 5, s2, 6)
+
+
+def test_attention_rule_flags_a_wrong_output():
+    c, q = make_case(21, lens=(13, 7))
+    pages = [0, 2]
+    o, lse = oracle.attention(c, q, 0, 1, pages)
+    out = torch.zeros((c.B, c.H, c.D))
+    lse_t = torch.zeros((c.B, c.H))
+    out[0, 1] = torch.from_numpy(o).float()
+    lse_t[0, 1] = lse
+    Hn.check_attention_head(out, lse_t, c, q, 0, 1, pages, torch.float32)
+    bad = out.clone()
+    bad[0, 1, 3] += 5e-4
+    with pytest.raises(AssertionError):
+        Hn.check_attention_head(bad, lse_t, c, q, 0, 1, pages, torch.float32)
+    with pytest.raises(AssertionError):                 # attended the wrong page set
+        Hn.check_attention_head(out, lse_t, c, q, 0, 1, [0, 3], torch.float32)
+    bad_lse = lse_t.clone()
+    bad_lse[0, 1] += 1e-2
+    with pytest.raises(AssertionError):
+        Hn.check_attention_head(out, bad_lse, c, q, 0, 1, pages, torch.float32)
