@@ -249,14 +249,21 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
 
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int row = b * c.Hkv + hkv;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int begin = split * pages_per_split;
+  // the first list entry of this lane is requested together with the lengths (row storage is sel_stride
+  // entries long, so the load does not have to wait for the count)
+  int first_lp = -1;
+  {
+    const int e = begin + wave + lane * kDecWaves;
+    if (sel_pages && e < min(begin + pages_per_split, sel_stride)) first_lp = sel_pages[(int64_t)row * sel_stride + e];
+  }
   const int N = c.seq_lens[b];
   const int P = min((N + S - 1) / S, c.max_pages_hint);
   const int cnt = sel_pages ? min(sel_count[row], sel_stride) : P;
-  const int begin = split * pages_per_split;
   if (begin >= cnt) return;
   const int end = min(begin + pages_per_split, cnt);
 
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int kt = lane % 16, kg = lane / 16;                       // K / logit layout: token slot, lane group
   const int vr_ = lane / kLanesPerTok, vc_ = lane % kLanesPerTok;  // V layout: token row inside a load, chunk
 
@@ -292,7 +299,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
     {
       const int e = e0 + lane * kDecWaves;
       if (e < end) {
-        const int lp = sel_pages ? sel_pages[(int64_t)row * sel_stride + e] : e;
+        const int lp = !sel_pages ? e : (e0 == begin + wave ? first_lp : sel_pages[(int64_t)row * sel_stride + e]);
         if (lp >= 0 && lp < P) {
           const int ph = c.page_table[(int64_t)b * c.max_pages + lp];
           if (ph >= 0 && (int64_t)ph < c.num_phys) {

@@ -8,8 +8,9 @@
 // page record, read as one contiguous block whatever the page table does to page placement, with
 // the page's stds taken from the tail of the same record. Every lane keeps its slices of the G
 // queries of its (fixed) KV head in registers for the whole kernel. The G partial dot products are
-// reduced over the 8 lanes with three DPP steps. Page-table entries for several steps are fetched
-// ahead of the record loads that depend on them. Scores of a tile are staged in LDS and written as
+// reduced over the 8 lanes with three DPP steps. The page-table entries of all of a wave's steps are
+// fetched up front (together with the sequence length and the queries, so the prologue is two memory
+// round trips) and the next step's record is requested before the current one is consumed. Scores of a tile are staged in LDS and written as
 // one contiguous run per KV head (4-byte scattered stores cost a tenth of the kernel otherwise).
 #include "device_utils.hpp"
 #include "kernels.hpp"
@@ -21,11 +22,7 @@ constexpr int kScoreWaves = 4;
 #ifndef UNIQUE_SCORE_TILE
 #define UNIQUE_SCORE_TILE 64
 #endif
-#ifndef UNIQUE_SCORE_UNROLL
-#define UNIQUE_SCORE_UNROLL 2
-#endif
 constexpr int kTilePages = UNIQUE_SCORE_TILE;  // logical pages per workgroup
-constexpr int kMaxKvHeads = 32;
 constexpr int kRowLanes = 8;                   // lanes per (page, head) row
 constexpr int kRowsPerWave = kWave / kRowLanes;
 
@@ -56,16 +53,9 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
                                                                         float* __restrict__ scores_out) {
   constexpr int kE = Elem<TS>::kVec;                 // mean elements per 16-byte load
   constexpr int kChunks = D / (kE * kRowLanes);      // 16-byte loads per lane per row
-  constexpr int kUnroll = (G * kChunks * kE > 64) ? (UNIQUE_SCORE_UNROLL / 2 > 0 ? UNIQUE_SCORE_UNROLL / 2 : 1)
-                                                  : UNIQUE_SCORE_UNROLL;
 
   const int b = blockIdx.y;
-  const int N = c.seq_lens[b];
-  const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
   const int tile0 = blockIdx.x * kTilePages;
-  if (tile0 >= P) return;
-  const int tile_end = min(tile0 + kTilePages, P);
-
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int row8 = lane / kRowLanes, cl = lane % kRowLanes;
   // which head and which page of a step this lane's row is; both fixed for the whole kernel
@@ -84,6 +74,22 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     wave_slot = wave;
     wave_slots = kScoreWaves;
   }
+  const int step_pages = wave_slots * pages_per_step;  // pages the workgroup advances per step
+
+  // The sequence length, the page ids of all of this wave's steps (lane L holds entry L = step *
+  // pages_per_step + page_in_step) and the queries are requested together; the page-table row always has
+  // max_pages readable entries, so its load does not have to wait for the page count.
+  const int32_t* pt = c.page_table + (int64_t)b * c.max_pages;
+  int my_page, my_phys_raw = -1;
+  {
+    const int st = lane / pages_per_step, po = lane % pages_per_step;
+    my_page = tile0 + (wave_slot + st * wave_slots) * pages_per_step + po;
+    if (my_page < min(tile0 + kTilePages, c.max_pages_hint)) my_phys_raw = pt[my_page];
+  }
+  const int N = c.seq_lens[b];
+  const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
+  if (tile0 >= P) return;
+  const int tile_end = min(tile0 + kTilePages, P);
 
   float qv[G][kChunks][kE];
   float off[G];
@@ -100,57 +106,55 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     off[g] = lambda * sqrtf(qq);
   }
 
-  const int32_t* pt = c.page_table + (int64_t)b * c.max_pages;
   const char* stats = reinterpret_cast<const char*>(c.page_stats);
   const int64_t std_off = (int64_t)c.Hkv * D * (int64_t)sizeof(TS);  // byte offset of the stds inside a record
-  const int step_pages = wave_slots * pages_per_step;  // pages the workgroup advances per step
-  __shared__ float tile_scores[kMaxKvHeads][kTilePages];
+  extern __shared__ float tile_scores[];  // [Hkv][kTilePages]
 
-  for (int base = tile0 + wave_slot * pages_per_step; base < tile_end; base += step_pages * kUnroll) {
-    const char* rec[kUnroll];
+  const int n_steps = (tile_end - (tile0 + wave_slot * pages_per_step) + step_pages - 1) / step_pages;  // may be <= 0
+  const int my_phys = (my_page < tile_end && my_phys_raw >= 0 && (int64_t)my_phys_raw < c.num_phys) ? my_phys_raw : -1;
+  Raw16 mc[kChunks], mn[kChunks];
+  float sd_cur = 0.f, sd_nxt = 0.f;
+  int phys_cur = -1, phys_nxt = -1;
+  auto issue = [&](int st, Raw16(&md)[kChunks], float& sd, int& phys) {
+    phys = pages_per_step == 1 ? __builtin_amdgcn_readlane(my_phys, st)
+                               : __shfl(my_phys, st * pages_per_step + page_in_step, kWave);
+    if (phys >= 0) {
+      const char* rec = stats + (int64_t)phys * c.rec_bytes;
+      const TS* row = reinterpret_cast<const TS*>(rec) + hkv * D + cl * kE;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int p = base + u * step_pages + page_in_step;
-      int64_t phys = -1;
-      if (p < tile_end) phys = pt[p];
-      rec[u] = (phys >= 0 && phys < c.num_phys) ? stats + phys * c.rec_bytes : nullptr;
+      for (int j = 0; j < kChunks; ++j) md[j] = load_raw_stream(row + j * (kE * kRowLanes), c.stream_nt);
+      sd = reinterpret_cast<const float*>(rec + std_off)[hkv];
+    } else {
+#pragma unroll
+      for (int j = 0; j < kChunks; ++j) md[j] = zero_raw();
+      sd = 0.f;
     }
-    Raw16 m[kUnroll][kChunks];
-    float sd[kUnroll];
+  };
+  if (n_steps > 0) issue(0, mc, sd_cur, phys_cur);
+  for (int st = 0; st < n_steps; ++st) {
+    if (st + 1 < n_steps) issue(st + 1, mn, sd_nxt, phys_nxt);
+    float mf[kChunks][kE];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      if (rec[u]) {
-        const TS* row = reinterpret_cast<const TS*>(rec[u]) + hkv * D + cl * kE;
+    for (int j = 0; j < kChunks; ++j) unpack_raw(mc[j], mf[j], (const TS*)nullptr);
+    float best = 0.f;
 #pragma unroll
-        for (int j = 0; j < kChunks; ++j) m[u][j] = load_raw_stream(row + j * (kE * kRowLanes), c.stream_nt);
-        sd[u] = reinterpret_cast<const float*>(rec[u] + std_off)[hkv];
-      } else {
+    for (int g = 0; g < G; ++g) {
+      float dot = 0.f;
 #pragma unroll
-        for (int j = 0; j < kChunks; ++j) m[u][j] = zero_raw();
-        sd[u] = 0.f;
-      }
+      for (int j = 0; j < kChunks; ++j)
+#pragma unroll
+        for (int i = 0; i < kE; ++i) dot = fmaf(qv[g][j][i], mf[j][i], dot);
+      dot = group_allreduce<kRowLanes>(dot, OpSum());
+      const float sc = fmaf(off[g], sd_cur, dot);
+      best = (g == 0) ? sc : fmaxf(best, sc);
     }
+    const int p = tile0 + (wave_slot + st * wave_slots) * pages_per_step + page_in_step;
+    // a page whose table entry points outside the pool gets NaN, which ranks below every score
+    if (cl == 0 && p < tile_end) tile_scores[hkv * kTilePages + p - tile0] = phys_cur >= 0 ? best : __uint_as_float(0x7fc00000u);
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      float mf[kChunks][kE];
-#pragma unroll
-      for (int j = 0; j < kChunks; ++j) unpack_raw(m[u][j], mf[j], (const TS*)nullptr);
-      float best = 0.f;
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float dot = 0.f;
-#pragma unroll
-        for (int j = 0; j < kChunks; ++j)
-#pragma unroll
-          for (int i = 0; i < kE; ++i) dot = fmaf(qv[g][j][i], mf[j][i], dot);
-        dot = group_allreduce<kRowLanes>(dot, OpSum());
-        const float s = fmaf(off[g], sd[u], dot);
-        best = (g == 0) ? s : fmaxf(best, s);
-      }
-      const int p = base + u * step_pages + page_in_step;
-      // a page whose table entry points outside the pool gets NaN, which ranks below every score
-      if (cl == 0 && p < tile_end) tile_scores[hkv][p - tile0] = rec[u] ? best : __uint_as_float(0x7fc00000u);
-    }
+    for (int j = 0; j < kChunks; ++j) mc[j] = mn[j];
+    sd_cur = sd_nxt;
+    phys_cur = phys_nxt;
   }
   __syncthreads();
   // the tile's scores leave as one contiguous run per KV head
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   for (int idx = threadIdx.x; idx < c.Hkv * kTilePages; idx += kScoreWaves * kWave) {
     const int h = idx / kTilePages, pp = idx % kTilePages;
     if (pp < tile_len) {
-      const float v = tile_scores[h][pp];
+      const float v = tile_scores[idx];
       scores[((int64_t)b * c.Hkv + h) * score_stride + tile0 + pp] = v;
       if (scores_out) scores_out[((int64_t)b * c.Hkv + h) * c.max_pages + tile0 + pp] = v;
     }
@@ -171,12 +175,13 @@ hipError_t launch_t(const CacheView& cv, const void* q, float lambda, float* sco
   CacheView c = cv;
   c.stream_nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
   dim3 grid((c.max_pages_hint + kTilePages - 1) / kTilePages, c.B), block(kScoreWaves * kWave);
+  const size_t lds = (size_t)c.Hkv * kTilePages * sizeof(float);
   if (c.stats_bf16)
-    page_score_kernel<T, bf16_t, D, G><<<grid, block, 0, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                               stride, out);
+    page_score_kernel<T, bf16_t, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
+                                                                 stride, out);
   else
-    page_score_kernel<T, float, D, G><<<grid, block, 0, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                              stride, out);
+    page_score_kernel<T, float, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
+                                                                stride, out);
   return hipGetLastError();
 }
 
