@@ -149,6 +149,19 @@ int unique_sparse_paged_decode(const unique_cache_desc* desc, const void* d_q, c
                                const int32_t* d_sel_count, int32_t sel_stride, float sm_scale, void* d_out,
                                float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* One whole decode step in a single call: [refresh of the last page's statistics +] Eq. 6 scores, top-k
+ * selection, Eq. 5 sparse attention. The results are bit-identical to unique_update_page_stats (on the last
+ * token of every sequence, when refresh_tail != 0) followed by unique_score_select_topk and
+ * unique_sparse_paged_decode with sel_stride = top_k; the statistics refresh runs inside the score kernel
+ * (the workgroup that scores the last page recomputes its record first, same arithmetic), which saves a launch.
+ *   refresh_tail : non-zero = recompute the statistics record of the page holding token seq_lens[b]-1 of every
+ *                  sequence before scoring (what a serving loop needs after appending one token).
+ *   outputs      : d_sel_pages / d_sel_count as unique_score_select_topk, d_out / d_lse_out as
+ *                  unique_sparse_paged_decode. The workspace needs unique_workspace_bytes(desc, top_k). */
+int unique_decode_step(const unique_cache_desc* desc, const void* d_q, int32_t top_k, float lambda, float sm_scale,
+                       int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out,
+                       float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream);
+
 /* Dense paged decode attention, Eq. 4: the same kernels with every page of each sequence attended. */
 int unique_dense_paged_decode(const unique_cache_desc* desc, const void* d_q, float sm_scale, void* d_out,
                               float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream);

@@ -18,7 +18,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 DTYPE_CODE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = ("unique_workspace_bytes", "unique_page_stats_record_bytes", "unique_update_page_stats", "unique_score_select_topk",
-           "unique_page_scores", "unique_select_topk", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
+           "unique_page_scores", "unique_select_topk", "unique_decode_step", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
            "unique_last_error", "unique_version")
 
 
@@ -69,6 +69,9 @@ class Library:
         self.c.unique_sparse_paged_decode.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                                       C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                                       C.c_size_t, C.c_void_p]
+        self.c.unique_decode_step.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_float, C.c_float,
+                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
         self.c.unique_dense_paged_decode.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_float, C.c_void_p,
                                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 
@@ -117,6 +120,12 @@ class Library:
         self.check(self.c.unique_sparse_paged_decode(C.byref(desc), _p(q), _p(sel_pages), _p(sel_count), sel_stride,
                                                      sm_scale, _p(out), _p(lse_out), _p(workspace),
                                                      workspace.numel() * workspace.element_size(), _stream()))
+
+    def decode_step(self, desc: CacheDesc, q, top_k: int, lam: float, sm_scale: float, refresh_tail: bool, sel_pages,
+                    sel_count, out, lse_out, workspace):
+        self.check(self.c.unique_decode_step(C.byref(desc), _p(q), top_k, lam, sm_scale, int(refresh_tail),
+                                             _p(sel_pages), _p(sel_count), _p(out), _p(lse_out), _p(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream()))
 
     def dense_paged_decode(self, desc: CacheDesc, q, sm_scale: float, out, lse_out, workspace):
         self.check(self.c.unique_dense_paged_decode(C.byref(desc), _p(q), sm_scale, _p(out), _p(lse_out),

@@ -98,6 +98,7 @@ size_t decode_bytes(const unique::CacheView& v, int max_list_len) {
   return unique::decode_partial_floats(v, max_list_len) * sizeof(float);
 }
 
+
 int check_workspace(const void* ws, size_t have, size_t need) {
   if (!ws) return fail(UNIQUE_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
   if ((uintptr_t)ws % kAlign) return fail(UNIQUE_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kAlign);
@@ -171,7 +172,7 @@ int unique_score_select_topk(const unique_cache_desc* desc, const void* d_q, int
   if (rc != UNIQUE_OK) return rc;
   float* scores = reinterpret_cast<float*>(d_workspace);
   const int stride = score_stride_of(v);
-  hipError_t e = unique::launch_score(v, d_q, lambda, scores, stride, d_scores_out, (hipStream_t)stream);
+  hipError_t e = unique::launch_score(v, d_q, lambda, scores, stride, d_scores_out, false, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "page score launch");
   e = unique::launch_select(v, scores, stride, top_k, d_sel_pages, d_sel_count, (hipStream_t)stream);
   return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "top-k select launch");
@@ -189,7 +190,7 @@ int unique_page_scores(const unique_cache_desc* desc, const void* d_q, float lam
   if (score_stride < v.max_pages_hint || score_stride % 4 != 0)
     return fail(UNIQUE_ERR_INVALID_ARG, "score_stride %d must be a multiple of 4 and >= %d pages", score_stride,
                 v.max_pages_hint);
-  const hipError_t e = unique::launch_score(v, d_q, lambda, d_scores, score_stride, nullptr, (hipStream_t)stream);
+  const hipError_t e = unique::launch_score(v, d_q, lambda, d_scores, score_stride, nullptr, false, (hipStream_t)stream);
   return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "page score launch");
 }
 
@@ -227,6 +228,36 @@ int unique_sparse_paged_decode(const unique_cache_desc* desc, const void* d_q, c
   if (rc != UNIQUE_OK) return rc;
   const hipError_t e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, sel_stride, list_len, sm_scale, d_out,
                                              d_lse_out, reinterpret_cast<float*>(d_workspace), (hipStream_t)stream);
+  return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "sparse decode launch");
+}
+
+int unique_decode_step(const unique_cache_desc* desc, const void* d_q, int32_t top_k, float lambda, float sm_scale,
+                       int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out,
+                       float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream) {
+  unique::CacheView v;
+  int rc = make_view(desc, &v, true, true);
+  if (rc != UNIQUE_OK) return rc;
+  if (!d_q || !d_sel_pages || !d_sel_count || !d_out)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_q, d_sel_pages, d_sel_count and d_out must be non-NULL");
+  if (((uintptr_t)d_q | (uintptr_t)d_out) & 15u)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_out must be 16-byte aligned");
+  if (top_k < 1) return fail(UNIQUE_ERR_INVALID_ARG, "top_k must be >= 1 (got %d)", top_k);
+  if (!(lambda >= 0.f)) return fail(UNIQUE_ERR_INVALID_ARG, "lambda must be >= 0");
+  if (!(sm_scale == sm_scale)) return fail(UNIQUE_ERR_INVALID_ARG, "sm_scale is NaN");
+  const int list_len = top_k < v.max_pages_hint ? top_k : v.max_pages_hint;
+  size_t region = score_bytes(v);
+  if (decode_bytes(v, list_len) > region) region = decode_bytes(v, list_len);
+  rc = check_workspace(d_workspace, workspace_bytes, region);
+  if (rc != UNIQUE_OK) return rc;
+  // the score rows are consumed by the select kernel before the decode kernel reuses the buffer for its partials
+  float* buf = reinterpret_cast<float*>(d_workspace);
+  const int stride = score_stride_of(v);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = unique::launch_score(v, d_q, lambda, buf, stride, nullptr, refresh_tail != 0, st);
+  if (e != hipSuccess) return hip_fail(e, "page score launch");
+  e = unique::launch_select(v, buf, stride, top_k, d_sel_pages, d_sel_count, st);
+  if (e != hipSuccess) return hip_fail(e, "top-k select launch");
+  e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, top_k, list_len, sm_scale, d_out, d_lse_out, buf, st);
   return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "sparse decode launch");
 }
 

@@ -41,8 +41,10 @@ bool decode_supported(int dtype, int D, int S, int G);
 hipError_t launch_stats(const CacheView& c, const int32_t* d_tok_begin, const int32_t* d_tok_end,
                         int max_pages_touched, hipStream_t stream);
 
+// refresh_tail: the workgroup that scores the last page of a sequence first recomputes that page's
+// statistics from the keys (the same arithmetic as launch_stats) and stores them.
 hipError_t launch_score(const CacheView& c, const void* d_q, float lambda, float* d_scores, int score_stride,
-                        float* d_scores_out, hipStream_t stream);
+                        float* d_scores_out, bool refresh_tail, hipStream_t stream);
 
 hipError_t launch_select(const CacheView& c, const float* d_scores, int score_stride, int top_k,
                          int32_t* d_sel_pages, int32_t* d_sel_count, hipStream_t stream);

@@ -45,12 +45,91 @@ __device__ __forceinline__ void load_q(const bf16_t* p, float (&out)[kE]) {
   }
 }
 
+// Statistics of the last (possibly partial) page of sequence b, recomputed from the keys by the whole
+// workgroup: wave w takes KV heads w, w+4, ... The lane layout, the order of every sum and the
+// cross-lane reductions are those of the bulk statistics kernel, so the stored record is bit-identical
+// to what unique_update_page_stats writes. The page size is a run-time value here, so the loads are
+// predicated up to the largest supported page (32 tokens).
+template <typename T, int D>
+__device__ __forceinline__ void refresh_tail_record(const CacheView& c, int b, int N, int P) {
+  constexpr int kVec = Elem<T>::kVec;
+  constexpr int kLanesPerTok = D / kVec;
+  constexpr int kTokPerLoad = kWave / kLanesPerTok;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int tr = lane / kLanesPerTok, ch = lane % kLanesPerTok;
+  const int p = P - 1, S = c.S;
+  const int n = min(S, N - p * S);
+  const int64_t phys = c.page_table[(int64_t)b * c.max_pages + p];
+  if (phys < 0 || phys >= c.num_phys || n < 1) return;
+  char* rec = reinterpret_cast<char*>(c.page_stats) + phys * c.rec_bytes;
+  const int64_t mean_bytes = (int64_t)c.Hkv * D * (c.stats_bf16 ? 2 : 4);
+  const float inv_n = 1.0f / (float)n;
+  constexpr int kMaxLoads = 32 / kTokPerLoad;  // page_size <= 32
+  for (int hkv = wave; hkv < c.Hkv; hkv += kScoreWaves) {
+    const T* base = reinterpret_cast<const T*>(c.k_cache) + ((phys * c.Hkv + hkv) * S) * (int64_t)D + ch * kVec;
+    // the page is read once and kept as raw 16-byte chunks; both passes unpack from registers
+    Raw16 raw[kMaxLoads];
+#pragma unroll
+    for (int j = 0; j < kMaxLoads; ++j) {
+      const int tok = j * kTokPerLoad + tr;
+      raw[j] = tok < n ? load_raw(base + (int64_t)tok * D) : zero_raw();
+    }
+    float sum[kVec];
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) sum[i] = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxLoads; ++j) {
+      if (j * kTokPerLoad + tr < n) {
+        float x[kVec];
+        unpack_raw(raw[j], x, (const T*)nullptr);
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) sum[i] += x[i];
+      }
+    }
+    float mean[kVec];
+#pragma unroll
+    for (int i = 0; i < kVec; ++i) mean[i] = cross_group_allreduce<kLanesPerTok>(sum[i], OpSum()) * inv_n;
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxLoads; ++j) {
+      if (j * kTokPerLoad + tr < n) {
+        float x[kVec];
+        unpack_raw(raw[j], x, (const T*)nullptr);
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+          const float dev = x[i] - mean[i];
+          ss = fmaf(dev, dev, ss);  // explicit: both statistics paths must round identically
+        }
+      }
+    }
+    ss = group_allreduce<kWave>(ss, OpSum());
+    if (tr == 0) {
+      if (c.stats_bf16) {
+        bf16_t* m = reinterpret_cast<bf16_t*>(rec) + hkv * D + ch * kVec;
+        uint32_t w[kVec / 2];
+#pragma unroll
+        for (int i = 0; i < kVec; i += 2)
+          w[i / 2] = (uint32_t)float_to_bf16(mean[i]) | ((uint32_t)float_to_bf16(mean[i + 1]) << 16);
+        if constexpr (kVec == 8) *reinterpret_cast<uint4*>(m) = make_uint4(w[0], w[1], w[2], w[3]);
+        else *reinterpret_cast<uint2*>(m) = make_uint2(w[0], w[1]);
+      } else {
+        float* m = reinterpret_cast<float*>(rec) + hkv * D + ch * kVec;
+#pragma unroll
+        for (int i = 0; i < kVec; i += 4)
+          *reinterpret_cast<float4*>(m + i) = make_float4(mean[i], mean[i + 1], mean[i + 2], mean[i + 3]);
+      }
+    }
+    if (lane == 0) reinterpret_cast<float*>(rec + mean_bytes)[hkv] = sqrtf(ss * inv_n);
+  }
+}
+
 // T: element type of q; TS: element type of the stored means (float, or bf16_t for bf16 statistics).
 template <typename T, typename TS, int D, int G>
 __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheView c, const T* __restrict__ q,
                                                                         float lambda, float* __restrict__ scores,
                                                                         int score_stride,
-                                                                        float* __restrict__ scores_out) {
+                                                                        float* __restrict__ scores_out,
+                                                                        int refresh_tail) {
   constexpr int kE = Elem<TS>::kVec;                 // mean elements per 16-byte load
   constexpr int kChunks = D / (kE * kRowLanes);      // 16-byte loads per lane per row
 
@@ -90,6 +169,11 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
   if (tile0 >= P) return;
   const int tile_end = min(tile0 + kTilePages, P);
+  if (refresh_tail && tile_end == P) {  // this workgroup scores the last page: bring its record up to date first
+    refresh_tail_record<T, D>(c, b, N, P);
+    __threadfence_block();
+    __syncthreads();
+  }
 
   float qv[G][kChunks][kE];
   float off[G];
@@ -171,28 +255,28 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
 
 template <typename T, int D, int G>
 hipError_t launch_t(const CacheView& cv, const void* q, float lambda, float* scores, int stride, float* out,
-                    hipStream_t st) {
+                    bool refresh_tail, hipStream_t st) {
   CacheView c = cv;
   c.stream_nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
   dim3 grid((c.max_pages_hint + kTilePages - 1) / kTilePages, c.B), block(kScoreWaves * kWave);
   const size_t lds = (size_t)c.Hkv * kTilePages * sizeof(float);
   if (c.stats_bf16)
     page_score_kernel<T, bf16_t, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                                 stride, out);
+                                                                 stride, out, refresh_tail);
   else
     page_score_kernel<T, float, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                                stride, out);
+                                                                stride, out, refresh_tail);
   return hipGetLastError();
 }
 
 template <typename T, int D>
 hipError_t dispatch_g(const CacheView& c, const void* q, float lambda, float* scores, int stride, float* out,
-                      hipStream_t st) {
+                      bool refresh_tail, hipStream_t st) {
   switch (c.H / c.Hkv) {
-    case 1: return launch_t<T, D, 1>(c, q, lambda, scores, stride, out, st);
-    case 2: return launch_t<T, D, 2>(c, q, lambda, scores, stride, out, st);
-    case 4: return launch_t<T, D, 4>(c, q, lambda, scores, stride, out, st);
-    case 8: return launch_t<T, D, 8>(c, q, lambda, scores, stride, out, st);
+    case 1: return launch_t<T, D, 1>(c, q, lambda, scores, stride, out, refresh_tail, st);
+    case 2: return launch_t<T, D, 2>(c, q, lambda, scores, stride, out, refresh_tail, st);
+    case 4: return launch_t<T, D, 4>(c, q, lambda, scores, stride, out, refresh_tail, st);
+    case 8: return launch_t<T, D, 8>(c, q, lambda, scores, stride, out, refresh_tail, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -207,13 +291,13 @@ bool score_supported(int dtype, int D, int G, int Hkv) {
 }
 
 hipError_t launch_score(const CacheView& c, const void* d_q, float lambda, float* d_scores, int score_stride,
-                        float* d_scores_out, hipStream_t stream) {
+                        float* d_scores_out, bool refresh_tail, hipStream_t stream) {
   if (c.dtype == 0) {
-    return c.D == 64 ? dispatch_g<float, 64>(c, d_q, lambda, d_scores, score_stride, d_scores_out, stream)
-                     : dispatch_g<float, 128>(c, d_q, lambda, d_scores, score_stride, d_scores_out, stream);
+    return c.D == 64 ? dispatch_g<float, 64>(c, d_q, lambda, d_scores, score_stride, d_scores_out, refresh_tail, stream)
+                     : dispatch_g<float, 128>(c, d_q, lambda, d_scores, score_stride, d_scores_out, refresh_tail, stream);
   }
-  return c.D == 64 ? dispatch_g<bf16_t, 64>(c, d_q, lambda, d_scores, score_stride, d_scores_out, stream)
-                   : dispatch_g<bf16_t, 128>(c, d_q, lambda, d_scores, score_stride, d_scores_out, stream);
+  return c.D == 64 ? dispatch_g<bf16_t, 64>(c, d_q, lambda, d_scores, score_stride, d_scores_out, refresh_tail, stream)
+                   : dispatch_g<bf16_t, 128>(c, d_q, lambda, d_scores, score_stride, d_scores_out, refresh_tail, stream);
 }
 
 }  // namespace unique

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
 #pragma unroll
       for (int i = 0; i < kVec; ++i) {
         const float dev = x[j][i] - mean[i];
-        ss += dev * dev;
+        ss = fmaf(dev, dev, ss);  // explicit: both statistics paths must round identically
       }
     }
   }

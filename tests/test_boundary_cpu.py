@@ -117,6 +117,14 @@ def test_call_argument_validation(lib):
     assert g(C.byref(d), 0x7004, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
     assert g(C.byref(d), 0x7000, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, 0, None) == binding.ERR_WORKSPACE
     assert g(C.byref(good_desc(v_cache=0)), 0x7000, 0x100, 0x200, 4, 0.0, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    # fused step
+    ds = c.unique_decode_step
+    assert ds(C.byref(d), None, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert ds(C.byref(d), 0x7000, 0, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert ds(C.byref(d), 0x7000, 4, -0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert ds(C.byref(d), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, None, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    assert ds(C.byref(d), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, 64, None) == binding.ERR_WORKSPACE
+    assert ds(C.byref(good_desc(page_stats=0)), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
     # dense decode
     h = c.unique_dense_paged_decode
     assert h(C.byref(d), 0x7000, 0.0, None, None, ws, nws, None) == binding.ERR_INVALID_ARG

@@ -261,6 +261,64 @@ def test_split_score_and_select_calls_match_the_fused_call(gpu_lib):
     assert torch.equal(sess.sel_pages, sel_f) and torch.equal(sess.sel_count, cnt_f)
 
 
+@pytest.mark.parametrize("stats_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("maker", ["c1", "c3", "c4", "c5", "shape_s8", "shape_f32"])
+def test_fused_decode_step_is_bit_identical_to_the_separate_calls(gpu_lib, maker, stats_dtype):
+    """unique_decode_step (3 launches) against update_page_stats + score_select_topk + sparse_paged_decode."""
+    wl = {
+        "c1": lambda: W.config1(),
+        "c3": lambda: W.config3(batch=3, context=8192 + 5, top_k=64),
+        "c4": lambda: W.config4(batch=7, min_context=100, max_context=9000, top_k=16, spare_tokens=64),
+        "c5": lambda: W.config5(batch=2, context=16384, top_k=300),
+        "shape_s8": lambda: W.build("s8", 11, dtype=torch.bfloat16, B=5, H=16, Hkv=2, D=64, S=8,
+                                    seq_lens=[1, 8, 9, 700, 333], top_k=20, key_mode="shift", permute=True, spare_tokens=40),
+        "shape_f32": lambda: W.build("f32", 12, dtype=torch.float32, B=3, H=8, Hkv=4, D=128, S=32,
+                                     seq_lens=[31, 32, 4000], top_k=5, key_mode="shift", permute=True, spare_tokens=40),
+    }[maker]().to(DEV)
+    ref = DecodeSession(wl, stats_dtype=stats_dtype)
+    fused = DecodeSession(wl, stats_dtype=stats_dtype)
+    ref.update_page_stats()
+    fused.update_page_stats()
+    spare = int(wl.meta.get("spare_tokens", 0))
+    for step in range(3 if spare else 1):
+        if spare:
+            W.append_tokens(wl, step)
+        end = wl.seq_lens.clone()
+        ref.update_page_stats(end - 1, end, 1)
+        ref.score_select_topk()
+        ref.sparse_paged_decode()
+        fused.decode_step(refresh_tail=True)
+        torch.cuda.synchronize()
+        assert torch.equal(ref.page_stats, fused.page_stats), "tail statistics differ"
+        assert torch.equal(ref.sel_pages, fused.sel_pages) and torch.equal(ref.sel_count, fused.sel_count)
+        assert torch.equal(ref.out.view(torch.uint8), fused.out.view(torch.uint8)), "outputs differ"
+        assert torch.equal(ref.lse, fused.lse)
+    # without the refresh the statistics are left alone
+    before = fused.page_stats.clone()
+    fused.decode_step(refresh_tail=False)
+    torch.cuda.synchronize()
+    assert torch.equal(before, fused.page_stats) and torch.equal(ref.out.view(torch.uint8), fused.out.view(torch.uint8))
+
+
+def test_fused_decode_step_against_the_oracle_with_appends(gpu_lib):
+    wl = W.config4(batch=6, min_context=300, max_context=6000, top_k=8, spare_tokens=64).to(DEV)
+    sess = DecodeSession(wl)
+    sess.update_page_stats()
+    for step in range(40):
+        W.append_tokens(wl, step)
+        sess.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    oc, q = Hn.oracle_cache(wl)
+    sel, cnt = sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy()
+    for b in range(wl.B):
+        for hkv in range(wl.Hkv):
+            mean_o, std_o = Hn.check_stats_row(sess, oc, b, hkv)
+            s_o = oracle.page_scores(oc, q, b, hkv, wl.lam, mean_o, std_o)
+            Hn.check_selection_row(sel[b, hkv], int(cnt[b, hkv]), s_o, sess.top_k, f"row ({b},{hkv})")
+            for g in range(wl.G):
+                Hn.check_attention_head(sess.out, sess.lse, oc, q, b, hkv * wl.G + g, sel[b, hkv, :cnt[b, hkv]], wl.dtype)
+
+
 def test_select_all_pages_equals_dense(gpu_lib):
     wl = W.config3(batch=2, context=4096 + 5, top_k=32).to(DEV)
     sess = DecodeSession(wl)
