@@ -31,12 +31,19 @@ def parse():
     ap.add_argument("--top-k", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--stats-dtype", default="fp32", choices=["fp32", "bf16"],
+                    help="storage of the page means: fp32 (selection equals an exact fp32 ranking) or bf16 (the paper's format)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="time the step as update_page_stats + score_select_topk + sparse_paged_decode instead of unique_decode_step")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="microbenchmarks at the shapes of the paper's Appendix A / B tables instead of a decode step")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes (counter calibration for rocprofv3 --pmc)")
     return ap.parse_args()
 
 
 def algorithmic_bytes(wl, sess, sel_count, seq_lens):
+    es = 2 if "bfloat16" in str(sess.stats_dtype) else 4  # bytes per stored mean element
     """Bytes the method itself must move per launch, per kernel (the numerators of achieved GB/s)."""
     e = 2 if str(wl.dtype).endswith("bfloat16") else 4
     S, D, G, Hkv, H, B = wl.S, wl.D, wl.G, wl.Hkv, wl.H, wl.B
@@ -45,9 +52,9 @@ def algorithmic_bytes(wl, sess, sel_count, seq_lens):
     out = {}
     # tail-page stats: the valid keys of the last page of each (b, hkv) read, D+1 floats written
     tail = [int(n) - (p - 1) * S for n, p in zip(seq_lens, pages)]
-    out["page_stats_kernel"] = sum(t * D * e * Hkv for t in tail) + B * Hkv * (D + 1) * 4
+    out["page_stats_kernel"] = sum(t * D * e * Hkv for t in tail) + B * Hkv * (D * es + 4)
     # score: mean + std read per (b, hkv, page), one page-table entry per (b, page), one float written
-    out["page_score_kernel"] = tot_pages * Hkv * (D * 4 + 4) + tot_pages * 4 + tot_pages * Hkv * 4 + B * H * D * e
+    out["page_score_kernel"] = tot_pages * Hkv * (D * es + 4) + tot_pages * 4 + tot_pages * Hkv * 4 + B * H * D * e
     # select: the score row read once, k_b + 1 ints written
     out["topk_select_kernel"] = tot_pages * Hkv * 4 + int(sel_count.sum()) * 4 + B * Hkv * 4
     # sparse decode: K and V of the selected pages (full pages; at most one per row is partial), list + table
@@ -83,12 +90,17 @@ def main():
     from paper_2605_27740_amd import workloads as W
     from paper_2605_27740_amd.session import DecodeSession
 
+    if args.paper_shapes:
+        paper_shapes(dev)
+        return
+    stats_dtype = torch.bfloat16 if args.stats_dtype == "bf16" else torch.float32
+
     t0 = time.time()
     kw = {} if args.top_k is None else {"top_k": args.top_k}
     wl = {"c2": W.config2, "c3": W.config3, "c4": W.config4, "c5": W.config5}[args.workload](device=dev, **kw)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
-    sess = DecodeSession(wl, want_scores=False)
+    sess = DecodeSession(wl, want_scores=False, stats_dtype=stats_dtype)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     # bulk statistics build (prefill-time work, reported but not part of the step)
@@ -101,10 +113,15 @@ def main():
     tok_end = wl.seq_lens.clone()
     tok_begin = tok_end - 1
 
-    def step():
+    def separate_step():
         sess.update_page_stats(tok_begin, tok_end, 1)
         sess.score_select_topk()
         sess.sparse_paged_decode()
+
+    def fused_step():  # the same work through the one-call entry point (tail refresh inside the score kernel)
+        sess.decode_step(refresh_tail=True)
+
+    step = separate_step if args.separate_calls else fused_step
 
     for _ in range(args.warmup):
         step()
@@ -117,6 +134,15 @@ def main():
     stop.record()
     torch.cuda.synchronize()
     ms_per_step = start.elapsed_time(stop) / args.steps
+    other = fused_step if args.separate_calls else separate_step
+    other()
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(args.steps):
+        other()
+    stop.record()
+    torch.cuda.synchronize()
+    other_us = start.elapsed_time(stop) / args.steps * 1e3
 
     # --- the same K steps again with an event between stages (stage breakdown; the events cost a little)
     # (score and select are launched through their own entry points here: the same two kernels as the fused call)
@@ -194,7 +220,9 @@ def main():
         "metric": "sparse decode attention us/step (tail-page stats + page score + top-k + sparse paged decode)",
         "value": us, "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "storage_dtype": str(wl.dtype).replace("torch.", ""), "data": "synthetic",
+        "dtype": "f32", "storage_dtype": str(wl.dtype).replace("torch.", ""), "stats_dtype": args.stats_dtype,
+        "data": "synthetic", "step_call": "separate calls" if args.separate_calls else "unique_decode_step",
+        "other_step_call_us": other_us,
         "config": {"workload": wl.name, "batch": wl.B, "q_heads": wl.H, "kv_heads": wl.Hkv, "head_dim": wl.D,
                    "page_size": wl.S, "context": max(seq_lens), "total_tokens": sum(seq_lens), "top_k_pages": sess.top_k,
                    "lambda": wl.lam},
@@ -207,6 +235,71 @@ def main():
         "paper_context": "paper: 11.4x attention-path speedup over dense FlashInfer at 32K, >=5.3x end to end (1x H100, S=8, batch 80)",
     }
     print(json.dumps(line))
+
+
+def paper_shapes(dev):
+    """Score kernel and top-k at the shapes of the paper's Appendix A (fused criticality kernel) and Appendix B
+    (radix top-k): batch 32, 32 q / 8 KV heads, D = 128, S = 8, lambda 0.5, k = 64, P = 1024 ... 16384; median of 100
+    timed iterations after 20 warm-ups (score) / 300 after 50 (top-k), as the paper does. The paper's numbers are one
+    H100 with bf16 scores; they are context, not a target."""
+    import torch
+    from paper_2605_27740_amd import workloads as W
+    from paper_2605_27740_amd.session import DecodeSession
+    paper_score_ms = {1024: 0.0388, 2048: 0.0589, 4096: 0.0990, 8192: 0.1804, 16384: 0.3422}
+    paper_topk_ms = {1024: 0.013, 2048: 0.013, 4096: 0.014, 8192: 0.018, 16384: 0.022}
+
+    def median_us(fn, n, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        xs = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        return xs[len(xs) // 2]
+
+    rows = []
+    for P in (1024, 2048, 4096, 8192, 16384):
+        wl = W.build(f"paper_appendix_P{P}", 6, dtype=torch.bfloat16, B=32, H=32, Hkv=8, D=128, S=8,
+                     seq_lens=[P * 8] * 32, top_k=64, key_mode="shift", plant_mode="none", permute=True,
+                     device=dev, poison=False)
+        row = {"pages": P, "kv_len": P * 8, "paper_h100_score_us": paper_score_ms[P] * 1e3,
+               "paper_h100_topk_us": paper_topk_ms[P] * 1e3}
+        stride = (wl.max_pages + 63) // 64 * 64
+        buf = torch.empty((wl.B, wl.Hkv, stride), device=dev, dtype=torch.float32)
+        for name, sd in (("fp32_stats", torch.float32), ("bf16_stats", torch.bfloat16)):
+            sess = DecodeSession(wl, want_scores=False, stats_dtype=sd)
+            sess.update_page_stats()
+            row[f"score_us_{name}"] = median_us(lambda: sess.page_scores(buf), 100, 20)
+            stat_bytes = wl.B * P * sess.page_stats.shape[1]
+            row[f"score_GBps_{name}"] = stat_bytes / row[f"score_us_{name}"] / 1e3
+            if sd == torch.float32:
+                row["topk_us"] = median_us(lambda: sess.select_topk(buf), 300, 50)
+                # Fig. 2 of the paper: attention over a 512-token budget (k = 64 pages of 8) vs dense
+                row["sparse_decode_us_k64"] = median_us(sess.sparse_paged_decode, 50, 10)
+                if P <= 4096:
+                    row["dense_decode_us"] = median_us(sess.dense_paged_decode, 10, 3)
+            del sess
+        rows.append(row)
+        del wl, buf
+        torch.cuda.empty_cache()
+    # Fig. 2 of the paper: 32 q / 8 KV heads, D = 128, S = 8, budget 512 tokens (k = 64 pages), batch 80, 32K context:
+    # score + top-k + sparse attention against dense attention (the paper: 11.4x over dense FlashInfer on one H100)
+    wl = W.build("paper_fig2_b80_32k", 6, dtype=torch.bfloat16, B=80, H=32, Hkv=8, D=128, S=8, seq_lens=[32768] * 80,
+                 top_k=64, key_mode="shift", plant_mode="none", permute=True, device=dev, poison=False)
+    fig2 = {"batch": 80, "kv_len": 32768, "budget_tokens": 512, "paper_h100_speedup_vs_dense_flashinfer": 11.4}
+    for name, sd in (("fp32_stats", torch.float32), ("bf16_stats", torch.bfloat16)):
+        sess = DecodeSession(wl, want_scores=False, stats_dtype=sd)
+        sess.update_page_stats()
+        fig2[f"sparse_path_us_{name}"] = median_us(lambda: sess.decode_step(refresh_tail=False), 100, 20)
+        if sd == torch.float32:
+            fig2["dense_us"] = median_us(sess.dense_paged_decode, 20, 5)
+        fig2[f"speedup_vs_own_dense_{name}"] = fig2["dense_us"] / fig2[f"sparse_path_us_{name}"]
+        del sess
+    print(json.dumps({"paper_shapes": {"batch": 32, "fig2": fig2, "q_heads": 32, "kv_heads": 8, "head_dim": 128, "page_size": 8,
+                                        "top_k_pages": 64, "lambda": 0.5, "rows": rows,
+                                        "note": "paper columns: one NVIDIA H100, bf16 scores (Appendix A and B); ours: one MI355X"}}))
 
 
 def measured_traffic(workload, kernel):

@@ -25,6 +25,7 @@ constexpr int kScoreWaves = 4;
 constexpr int kTilePages = UNIQUE_SCORE_TILE;  // logical pages per workgroup
 constexpr int kRowLanes = 8;                   // lanes per (page, head) row
 constexpr int kRowsPerWave = kWave / kRowLanes;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // kE consecutive query elements as floats (kE = 4 or 8)
 template <int kE>
@@ -175,16 +176,29 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     __syncthreads();
   }
 
-  float qv[G][kChunks][kE];
+  // bf16 queries against bf16 means: packed bf16 pairs go straight into v_dot2_f32_bf16 (two products
+  // per instruction accumulated in fp32, no unpacking); every other combination multiplies in fp32.
+  constexpr bool kDot2 = sizeof(T) == 2 && sizeof(TS) == 2;
+  float qv[kDot2 ? 1 : G][kChunks][kE];
+  uint32_t qp[kDot2 ? G : 1][kChunks][kE / 2];
   float off[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float qq = 0.f;
 #pragma unroll
     for (int j = 0; j < kChunks; ++j) {
-      load_q<kE>(q + ((int64_t)b * c.H + hkv * G + g) * D + j * (kE * kRowLanes) + cl * kE, qv[g][j]);
+      const T* qsrc = q + ((int64_t)b * c.H + hkv * G + g) * D + j * (kE * kRowLanes) + cl * kE;
+      float qf[kE];
+      load_q<kE>(qsrc, qf);
 #pragma unroll
-      for (int i = 0; i < kE; ++i) qq = fmaf(qv[g][j][i], qv[g][j][i], qq);
+      for (int i = 0; i < kE; ++i) qq = fmaf(qf[i], qf[i], qq);
+      if constexpr (kDot2) {
+#pragma unroll
+        for (int i = 0; i < kE / 2; ++i) qp[g][j][i] = reinterpret_cast<const uint32_t*>(qsrc)[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < kE; ++i) qv[g][j][i] = qf[i];
+      }
     }
     qq = group_allreduce<kRowLanes>(qq, OpSum());
     off[g] = lambda * sqrtf(qq);
@@ -217,17 +231,30 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   if (n_steps > 0) issue(0, mc, sd_cur, phys_cur);
   for (int st = 0; st < n_steps; ++st) {
     if (st + 1 < n_steps) issue(st + 1, mn, sd_nxt, phys_nxt);
-    float mf[kChunks][kE];
+    float mf[kDot2 ? 1 : kChunks][kE];
+    if constexpr (!kDot2) {
 #pragma unroll
-    for (int j = 0; j < kChunks; ++j) unpack_raw(mc[j], mf[j], (const TS*)nullptr);
+      for (int j = 0; j < kChunks; ++j) unpack_raw(mc[j], mf[j], (const TS*)nullptr);
+    }
     float best = 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float dot = 0.f;
+      if constexpr (kDot2) {
 #pragma unroll
-      for (int j = 0; j < kChunks; ++j)
+        for (int j = 0; j < kChunks; ++j) {
+          const uint32_t mw[4] = {mc[j].v.x, mc[j].v.y, mc[j].v.z, mc[j].v.w};
 #pragma unroll
-        for (int i = 0; i < kE; ++i) dot = fmaf(qv[g][j][i], mf[j][i], dot);
+          for (int i = 0; i < 4; ++i)
+            dot = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, qp[g][j][i]),
+                                                  __builtin_bit_cast(bf16x2_t, mw[i]), dot, false);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < kChunks; ++j)
+#pragma unroll
+          for (int i = 0; i < kE; ++i) dot = fmaf(qv[g][j][i], mf[j][i], dot);
+      }
       dot = group_allreduce<kRowLanes>(dot, OpSum());
       const float sc = fmaf(off[g], sd_cur, dot);
       best = (g == 0) ? sc : fmaxf(best, sc);
