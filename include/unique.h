@@ -25,6 +25,7 @@
  *
  * Memory layout (row-major, innermost last)
  *   k_cache, v_cache : [num_phys_pages][num_kv_heads][page_size][head_dim]   dtype
+ *                      (page and head strides may be widened, see kv_page_stride / kv_head_stride)
  *   page_stats       : one record per physical page, unique_page_stats_record_bytes(desc) bytes each:
  *                      the mean vectors of its KV heads (head h at elements [h*D, (h+1)*D), element type
  *                      float for stats_dtype fp32, bf16 for stats_dtype bf16), then the scalar stds as
@@ -84,6 +85,12 @@ typedef struct unique_cache_desc {
                                 format, half the bytes of the score stage); scores and selection are then exact
                                 with respect to the STORED statistics. The std is fp32 in both. */
   int32_t reserved;          /* must be 0 */
+  int64_t kv_page_stride;    /* elements between consecutive physical pages of k_cache (the same for v_cache);
+                                0 = H_kv*S*D (pages packed) */
+  int64_t kv_head_stride;    /* elements between consecutive KV heads inside a page; 0 = S*D (heads packed).
+                                The S*D elements of one (page, head) are always contiguous. Setting
+                                v_cache = k_cache + S*D, kv_head_stride = 2*S*D and kv_page_stride = H_kv*2*S*D
+                                describes a cache that keeps the K and V tiles of a (page, head) side by side. */
 } unique_cache_desc;
 
 /* Bytes of device workspace that any of the calls below may need for this descriptor and top_k

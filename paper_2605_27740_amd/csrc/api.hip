@@ -62,6 +62,15 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
   if (d->stats_dtype != UNIQUE_DTYPE_F32 && d->stats_dtype != UNIQUE_DTYPE_BF16)
     return fail(UNIQUE_ERR_INVALID_ARG, "stats_dtype %d is neither fp32 (0) nor bf16 (1)", d->stats_dtype);
   if (d->reserved != 0) return fail(UNIQUE_ERR_INVALID_ARG, "reserved field must be 0");
+  {
+    const int64_t tile = (int64_t)d->page_size * d->head_dim;
+    const int64_t hs = d->kv_head_stride ? d->kv_head_stride : tile;
+    const int64_t ps = d->kv_page_stride ? d->kv_page_stride : (int64_t)d->num_kv_heads * hs;
+    const int64_t vec = d->dtype == UNIQUE_DTYPE_BF16 ? 8 : 4;  // elements per 16-byte load
+    if (hs < tile || ps < (int64_t)d->num_kv_heads * hs || hs % vec != 0 || ps % vec != 0)
+      return fail(UNIQUE_ERR_INVALID_ARG, "kv_head_stride %lld / kv_page_stride %lld: need head stride >= S*D, page "
+                  "stride >= H_kv * head stride, both multiples of 16 bytes", (long long)hs, (long long)ps);
+  }
 
   v->k_cache = d->k_cache;
   v->v_cache = d->v_cache;
@@ -85,6 +94,9 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
   v->stats_bf16 = d->stats_dtype == UNIQUE_DTYPE_BF16;
   v->rec_bytes = unique_page_stats_record_bytes(d);
   v->stream_nt = 0;
+  const int64_t tile = (int64_t)d->page_size * d->head_dim;
+  v->kv_head_stride = d->kv_head_stride ? d->kv_head_stride : tile;
+  v->kv_page_stride = d->kv_page_stride ? d->kv_page_stride : (int64_t)d->num_kv_heads * v->kv_head_stride;
   return UNIQUE_OK;
 }
 

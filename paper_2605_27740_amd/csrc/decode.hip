@@ -16,7 +16,10 @@
 namespace unique {
 namespace {
 
-constexpr int kDecWaves = 4;
+#ifndef UNIQUE_DEC_WAVES
+#define UNIQUE_DEC_WAVES 4
+#endif
+constexpr int kDecWaves = UNIQUE_DEC_WAVES;
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no logit seen yet"
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
       const int phys = __builtin_amdgcn_readlane(my_phys, ent);
       ntok = __builtin_amdgcn_readlane(my_ntok, ent);
       tbase = (it % kTilesPerPage) * kTileLoads * kTokPerLoad;
-      const int64_t page_off = ((int64_t)phys * c.Hkv + hkv) * (int64_t)(S * D) + lane_off;
+      const int64_t page_off = (int64_t)phys * c.kv_page_stride + (int64_t)hkv * c.kv_head_stride + lane_off;
 #pragma unroll
       for (int j = 0; j < kTileLoads; ++j) {
         const int tok = tbase + j * kTokPerLoad + tr;
@@ -291,8 +294,8 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
 
   const bf16_t* kc = reinterpret_cast<const bf16_t*>(c.k_cache);
   const bf16_t* vc = reinterpret_cast<const bf16_t*>(c.v_cache);
-  const int64_t head_off = (int64_t)hkv * (S * D);
-  const int64_t page_stride = (int64_t)c.Hkv * (S * D);
+  const int64_t head_off = (int64_t)hkv * c.kv_head_stride;
+  const int64_t page_stride = c.kv_page_stride;
 
   for (int e0 = begin + wave; e0 < end; e0 += kDecWaves * kWave) {
     int my_phys = 0, my_ntok = 0;
@@ -326,8 +329,11 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       }
     };
 
-    Raw16 kr[kSteps], vr[kVLoads], kn[kSteps], vn[kVLoads];
-    bool kvalid_cur = false, kvalid_nxt = false;
+    // Three register buffers: while tile i is consumed, the loads of tiles i+1 and i+2 are in flight, so a
+    // wave is not paced by one memory round trip per tile. The loop is unrolled by three so that buffer
+    // roles are static (no register copies, and the waits only cover the oldest tile).
+    Raw16 kb0[kSteps], vb0[kVLoads], kb1[kSteps], vb1[kVLoads], kb2[kSteps], vb2[kVLoads];
+    bool kv0 = false, kv1 = false, kv2 = false;
     auto issue = [&](int tile, Raw16(&kd)[kSteps], Raw16(&vd)[kVLoads], bool& kvalid) {
       int phys, ntok, tok;
       slot_info(tile * kTile + kt, phys, ntok, tok);
@@ -342,11 +348,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
         vd[j] = tok < ntok ? load_raw_stream(vp, c.stream_nt) : zero_raw();
       }
     };
-
-    issue(0, kr, vr, kvalid_cur);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-      if (tile + 1 < n_tiles) issue(tile + 1, kn, vn, kvalid_nxt);
-
+    auto consume = [&](const Raw16(&kr)[kSteps], const Raw16(&vr)[kVLoads], bool kvalid_cur) {
       f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < kSteps; ++s)
@@ -394,12 +396,19 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
+    };
 
-#pragma unroll
-      for (int s = 0; s < kSteps; ++s) kr[s] = kn[s];
-#pragma unroll
-      for (int j = 0; j < kVLoads; ++j) vr[j] = vn[j];
-      kvalid_cur = kvalid_nxt;
+    issue(0, kb0, vb0, kv0);
+    if (n_tiles > 1) issue(1, kb1, vb1, kv1);
+    for (int tile = 0; tile < n_tiles; tile += 3) {
+      if (tile + 2 < n_tiles) issue(tile + 2, kb2, vb2, kv2);
+      consume(kb0, vb0, kv0);
+      if (tile + 1 >= n_tiles) break;
+      if (tile + 3 < n_tiles) issue(tile + 3, kb0, vb0, kv0);
+      consume(kb1, vb1, kv1);
+      if (tile + 2 >= n_tiles) break;
+      if (tile + 4 < n_tiles) issue(tile + 4, kb1, vb1, kv1);
+      consume(kb2, vb2, kv2);
     }
   }
 
@@ -543,7 +552,10 @@ SplitPlan plan_splits(int rows, int max_list_len) {
   if (max_list_len < 1) max_list_len = 1;
   const int wanted = (kTargetGroups + rows - 1) / rows;
   int pps = (max_list_len + wanted - 1) / wanted;
-  if (pps < 2 * kDecWaves) pps = 2 * kDecWaves;
+#ifndef UNIQUE_DEC_MIN_PAGES_PER_WAVE
+#define UNIQUE_DEC_MIN_PAGES_PER_WAVE 2
+#endif
+  if (pps < UNIQUE_DEC_MIN_PAGES_PER_WAVE * kDecWaves) pps = UNIQUE_DEC_MIN_PAGES_PER_WAVE * kDecWaves;
   // long lists are cut into many equal chunks so that ragged batches balance across the CUs
   if (pps > UNIQUE_DEC_MAX_PPS) pps = UNIQUE_DEC_MAX_PPS;
   pps = (pps + kDecWaves - 1) / kDecWaves * kDecWaves;

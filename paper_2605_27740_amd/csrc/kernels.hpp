@@ -19,6 +19,8 @@ struct CacheView {
   int32_t stats_bf16;         // 1: means stored as bf16, 0: fp32
   int64_t rec_bytes;          // bytes per page record of page_stats
   int32_t stream_nt;          // set per launch: read the streamed operand with non-temporal loads
+  int64_t kv_page_stride;     // elements between consecutive physical pages of k_cache (and of v_cache)
+  int64_t kv_head_stride;     // elements between consecutive KV heads inside a page
 };
 
 // Launches that stream more than this many bytes bypass cache allocation (the Infinity Cache holds 256 MB).

@@ -67,7 +67,7 @@ __device__ __forceinline__ void refresh_tail_record(const CacheView& c, int b, i
   const float inv_n = 1.0f / (float)n;
   constexpr int kMaxLoads = 32 / kTokPerLoad;  // page_size <= 32
   for (int hkv = wave; hkv < c.Hkv; hkv += kScoreWaves) {
-    const T* base = reinterpret_cast<const T*>(c.k_cache) + ((phys * c.Hkv + hkv) * S) * (int64_t)D + ch * kVec;
+    const T* base = reinterpret_cast<const T*>(c.k_cache) + phys * c.kv_page_stride + hkv * c.kv_head_stride + ch * kVec;
     // the page is read once and kept as raw 16-byte chunks; both passes unpack from registers
     Raw16 raw[kMaxLoads];
 #pragma unroll

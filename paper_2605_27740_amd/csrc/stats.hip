@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
 
   const int tr = lane / kLanesPerTok;  // key row inside one load
   const int ch = lane % kLanesPerTok;  // 16-byte chunk of the key
-  const T* base = reinterpret_cast<const T*>(c.k_cache) + ((phys * c.Hkv + hkv) * S) * (int64_t)D + ch * kVec;
+  const T* base = reinterpret_cast<const T*>(c.k_cache) + phys * c.kv_page_stride + hkv * c.kv_head_stride + ch * kVec;
 
   float x[kLoads][kVec];
   float sum[kVec];

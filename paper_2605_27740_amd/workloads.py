@@ -222,6 +222,16 @@ def config5(device="cpu", *, batch=4, context=262144, top_k=256, poison=True) ->
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
+def interleave_kv(wl: Workload) -> Workload:
+    """The same cache contents with the K and V tiles of every (page, head) side by side in one buffer
+    [num_phys_pages][Hkv][2][S][D]; k_cache / v_cache become strided views into it (same bits, other layout)."""
+    kv = torch.stack([wl.k_cache, wl.v_cache], dim=2).contiguous()
+    kw = dict(wl.__dict__)
+    kw["k_cache"], kw["v_cache"] = kv[:, :, 0], kv[:, :, 1]
+    kw["meta"] = dict(wl.meta, interleaved_kv=True)
+    return Workload(**kw)
+
+
 def append_tokens(wl: Workload, step: int) -> None:
     """Write one new (k, v) token per sequence into its next free slot and bump seq_lens (config 4's
     decode loop). Draws are seeded by (config, step); this is the serving engine's cache write."""

@@ -319,6 +319,28 @@ def test_fused_decode_step_against_the_oracle_with_appends(gpu_lib):
                 Hn.check_attention_head(sess.out, sess.lse, oc, q, b, hkv * wl.G + g, sel[b, hkv, :cnt[b, hkv]], wl.dtype)
 
 
+@pytest.mark.parametrize("maker", ["c1", "c3", "s8"])
+def test_strided_cache_with_k_and_v_side_by_side(gpu_lib, maker):
+    """kv_page_stride / kv_head_stride: K and V tiles of a (page, head) interleaved in one buffer give the same
+    bits as the packed layout, and match the oracle."""
+    wl = {"c1": lambda: W.config1(),
+          "c3": lambda: W.config3(batch=2, context=8192 + 9, top_k=64),
+          "s8": lambda: W.build("s8", 13, dtype=torch.bfloat16, B=3, H=8, Hkv=8, D=64, S=8, seq_lens=[5, 64, 1000],
+                                top_k=12, key_mode="shift", permute=True)}[maker]().to(DEV)
+    packed = DecodeSession(wl)
+    packed.update_page_stats()
+    packed.sparse_step()
+    packed.dense_paged_decode()
+    wl2 = W.interleave_kv(wl)
+    assert wl2.k_cache.stride(1) == 2 * wl.S * wl.D and wl2.v_cache.data_ptr() == wl2.k_cache.data_ptr() + wl.S * wl.D * wl.k_cache.element_size()
+    inter, rep = Hn.full_check(wl2)
+    say(rep)
+    for a, b in [(packed.page_stats, inter.page_stats), (packed.sel_pages, inter.sel_pages), (packed.lse, inter.lse),
+                 (packed.out.view(torch.uint8), inter.out.view(torch.uint8)),
+                 (packed.out_dense.view(torch.uint8), inter.out_dense.view(torch.uint8))]:
+        assert torch.equal(a, b)
+
+
 def test_select_all_pages_equals_dense(gpu_lib):
     wl = W.config3(batch=2, context=4096 + 5, top_k=32).to(DEV)
     sess = DecodeSession(wl)
