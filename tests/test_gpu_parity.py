@@ -341,6 +341,49 @@ def test_strided_cache_with_k_and_v_side_by_side(gpu_lib, maker):
         assert torch.equal(a, b)
 
 
+def test_sequence_length_hint_contract(gpu_lib):
+    """max_seq_len_hint = 0 means the page-table width; a hint below the real length cuts the sequence at the
+    hinted page count in every kernel (documented: the hint has to be a true upper bound)."""
+    wl = W.config3(batch=2, context=4096 + 3, top_k=16).to(DEV)
+    a = DecodeSession(wl)                       # hint = real maximum
+    b = DecodeSession(wl, max_seq_len_hint=0)   # hint from the page-table width
+    for s_ in (a, b):
+        s_.update_page_stats()
+        s_.sparse_step()
+        s_.dense_paged_decode()
+    torch.cuda.synchronize()
+    for x, y in [(a.sel_pages, b.sel_pages), (a.out.view(torch.uint8), b.out.view(torch.uint8)), (a.lse_dense, b.lse_dense),
+                 (a.page_stats, b.page_stats)]:
+        assert torch.equal(x, y)
+    short = DecodeSession(wl, max_seq_len_hint=1024)    # 64 of the 257 pages
+    short.update_page_stats()
+    short.sparse_step()
+    short.dense_paged_decode()
+    torch.cuda.synchronize()
+    assert int(short.sel_pages.max()) < 64 and (short.sel_count == 16).all()
+    oc, q = Hn.oracle_cache(wl)
+    Hn.check_attention_head(short.out_dense, short.lse_dense, oc, q, 1, 5, np.arange(64, dtype=np.int32), wl.dtype)
+    used = wl.page_table[:, :64].long().flatten()
+    rest = wl.page_table[:, 64:wl.num_pages(0)].long().flatten()
+    assert torch.isfinite(short.page_std[used]).all() and (short.page_stats[rest] == 0xFF).all()
+
+
+def test_calls_on_a_side_stream(gpu_lib):
+    """Every call enqueues on the stream it is given (here a non-default torch stream) and nowhere else."""
+    wl = W.config3(batch=2, context=8192, top_k=32).to(DEV)
+    ref = DecodeSession(wl)
+    ref.update_page_stats()
+    ref.sparse_step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    sess = DecodeSession(wl)
+    with torch.cuda.stream(side):
+        sess.update_page_stats()
+        sess.decode_step(refresh_tail=True)
+    side.synchronize()
+    assert torch.equal(ref.sel_pages, sess.sel_pages) and torch.equal(ref.out.view(torch.uint8), sess.out.view(torch.uint8))
+
+
 def test_select_all_pages_equals_dense(gpu_lib):
     wl = W.config3(batch=2, context=4096 + 5, top_k=32).to(DEV)
     sess = DecodeSession(wl)
