@@ -341,6 +341,37 @@ def test_strided_cache_with_k_and_v_side_by_side(gpu_lib, maker):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape_sweep(gpu_lib, seed):
+    """Seeded random draws over every supported (dtype, D, S, G, Hkv), ragged lengths, k, statistics format and
+    cache layout; all rows checked against the oracle through the one-call step and the separate calls."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = [torch.bfloat16, torch.float32][int(rng.integers(2))]
+    D = int(rng.choice([64, 128]))
+    S = int(rng.choice([8, 16, 32]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 4, 8, 16]))
+    B = int(rng.integers(1, 5))
+    lens = [int(x) for x in np.exp(rng.uniform(np.log(1), np.log(3000), size=B)).round().clip(1, 3000)]
+    top_k = int(rng.choice([1, 3, 17, 64, 200]))
+    stats_dtype = [torch.float32, torch.bfloat16][int(rng.integers(2))]
+    key_mode = ["iid", "shift", "ar1"][int(rng.integers(3))]
+    say(f"seed {seed}: {dtype} D={D} S={S} G={G} Hkv={Hkv} lens={lens} k={top_k} stats={stats_dtype} keys={key_mode}")
+    wl = W.build("sweep", 20 + seed, dtype=dtype, B=B, H=G * Hkv, Hkv=Hkv, D=D, S=S, seq_lens=lens, top_k=top_k,
+                 key_mode=key_mode, plant_mode="one_percent", permute=bool(rng.integers(2)), spare_tokens=S).to(DEV)
+    if rng.integers(2):
+        wl = W.interleave_kv(wl)
+    sess, rep = Hn.full_check(wl, stats_dtype=stats_dtype)
+    say(rep)
+    keep = (sess.sel_pages.clone(), sess.out.clone(), sess.lse.clone())
+    sess.sel_pages.fill_(-3)
+    sess.out.zero_()
+    sess.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    assert torch.equal(keep[0], sess.sel_pages) and torch.equal(keep[2], sess.lse)
+    assert torch.equal(keep[1].view(torch.uint8), sess.out.view(torch.uint8))
+
+
 def test_sequence_length_hint_contract(gpu_lib):
     """max_seq_len_hint = 0 means the page-table width; a hint below the real length cuts the sequence at the
     hinted page count in every kernel (documented: the hint has to be a true upper bound)."""
