@@ -10,8 +10,9 @@
 // queries of its (fixed) KV head in registers for the whole kernel. The G partial dot products are
 // reduced over the 8 lanes with three DPP steps. The page-table entries of all of a wave's steps are
 // fetched up front (together with the sequence length and the queries, so the prologue is two memory
-// round trips) and the next step's record is requested before the current one is consumed. Scores of a tile are staged in LDS and written as
-// one contiguous run per KV head (4-byte scattered stores cost a tenth of the kernel otherwise).
+// round trips); two records are in flight per wave, requested with unconditional loads so that the
+// loop is straight-line code with exact waits. Scores of a tile are staged in LDS and written as one
+// contiguous run per KV head (4-byte scattered stores cost a tenth of the kernel otherwise).
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -19,10 +20,12 @@ namespace unique {
 namespace {
 
 constexpr int kScoreWaves = 4;
-#ifndef UNIQUE_SCORE_TILE
-#define UNIQUE_SCORE_TILE 64
+#ifndef UNIQUE_SCORE_DEPTH
+#define UNIQUE_SCORE_DEPTH 2
 #endif
-constexpr int kTilePages = UNIQUE_SCORE_TILE;  // logical pages per workgroup
+#ifndef UNIQUE_SCORE_FAT_GRID
+#define UNIQUE_SCORE_FAT_GRID 4096  // workgroups above which a launch can afford the next larger tile
+#endif
 constexpr int kRowLanes = 8;                   // lanes per (page, head) row
 constexpr int kRowsPerWave = kWave / kRowLanes;
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -125,17 +128,19 @@ __device__ __forceinline__ void refresh_tail_record(const CacheView& c, int b, i
 }
 
 // T: element type of q; TS: element type of the stored means (float, or bf16_t for bf16 statistics).
-template <typename T, typename TS, int D, int G>
+// kNT: the records are read with non-temporal loads (a launch that streams more than the caches hold).
+template <typename T, typename TS, int D, int G, bool kNT>
 __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheView c, const T* __restrict__ q,
                                                                         float lambda, float* __restrict__ scores,
                                                                         int score_stride,
                                                                         float* __restrict__ scores_out,
-                                                                        int refresh_tail) {
+                                                                        int refresh_tail, int tile_pages) {
   constexpr int kE = Elem<TS>::kVec;                 // mean elements per 16-byte load
   constexpr int kChunks = D / (kE * kRowLanes);      // 16-byte loads per lane per row
+  constexpr int kDepth = UNIQUE_SCORE_DEPTH;          // records in flight per wave (deeper rings measured no faster)
 
   const int b = blockIdx.y;
-  const int tile0 = blockIdx.x * kTilePages;
+  const int tile0 = blockIdx.x * tile_pages;  // tile_pages logical pages per workgroup (32, 64 or 128)
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int row8 = lane / kRowLanes, cl = lane % kRowLanes;
   // which head and which page of a step this lane's row is; both fixed for the whole kernel
@@ -164,12 +169,12 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   {
     const int st = lane / pages_per_step, po = lane % pages_per_step;
     my_page = tile0 + (wave_slot + st * wave_slots) * pages_per_step + po;
-    if (my_page < min(tile0 + kTilePages, c.max_pages_hint)) my_phys_raw = pt[my_page];
+    if (my_page < min(tile0 + tile_pages, c.max_pages_hint)) my_phys_raw = pt[my_page];
   }
   const int N = c.seq_lens[b];
   const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
   if (tile0 >= P) return;
-  const int tile_end = min(tile0 + kTilePages, P);
+  const int tile_end = min(tile0 + tile_pages, P);
   if (refresh_tail && tile_end == P) {  // this workgroup scores the last page: bring its record up to date first
     refresh_tail_record<T, D>(c, b, N, P);
     __threadfence_block();
@@ -206,31 +211,30 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
 
   const char* stats = reinterpret_cast<const char*>(c.page_stats);
   const int64_t std_off = (int64_t)c.Hkv * D * (int64_t)sizeof(TS);  // byte offset of the stds inside a record
-  extern __shared__ float tile_scores[];  // [Hkv][kTilePages]
+  extern __shared__ float tile_scores[];  // [Hkv][tile_pages]
 
   const int n_steps = (tile_end - (tile0 + wave_slot * pages_per_step) + step_pages - 1) / step_pages;  // may be <= 0
   const int my_phys = (my_page < tile_end && my_phys_raw >= 0 && (int64_t)my_phys_raw < c.num_phys) ? my_phys_raw : -1;
-  Raw16 mc[kChunks], mn[kChunks];
-  float sd_cur = 0.f, sd_nxt = 0.f;
-  int phys_cur = -1, phys_nxt = -1;
+
+  // A ring of kDepth records is in flight per wave. The loads are unconditional -- a step past the end
+  // of the tile, or one whose page id is invalid, reads the first bytes of the statistics instead, which
+  // costs no memory traffic -- so the loop is straight-line code and every wait names the exact number of
+  // requests that may stay outstanding.
+  Raw16 ring[kDepth][kChunks];
+  float ring_sd[kDepth];
+  int ring_phys[kDepth];
   auto issue = [&](int st, Raw16(&md)[kChunks], float& sd, int& phys) {
-    phys = pages_per_step == 1 ? __builtin_amdgcn_readlane(my_phys, st)
-                               : __shfl(my_phys, st * pages_per_step + page_in_step, kWave);
-    if (phys >= 0) {
-      const char* rec = stats + (int64_t)phys * c.rec_bytes;
-      const TS* row = reinterpret_cast<const TS*>(rec) + hkv * D + cl * kE;
+    const int src_lane = min(st * pages_per_step + page_in_step, kWave - 1);
+    const int ph = pages_per_step == 1 ? __builtin_amdgcn_readlane(my_phys, min(st, kWave - 1))
+                                       : __shfl(my_phys, src_lane, kWave);
+    phys = st < n_steps ? ph : -1;
+    const char* rec = stats + (int64_t)max(phys, 0) * c.rec_bytes;
+    const TS* row = phys >= 0 ? reinterpret_cast<const TS*>(rec) + hkv * D + cl * kE : reinterpret_cast<const TS*>(stats);
 #pragma unroll
-      for (int j = 0; j < kChunks; ++j) md[j] = load_raw_stream(row + j * (kE * kRowLanes), c.stream_nt);
-      sd = reinterpret_cast<const float*>(rec + std_off)[hkv];
-    } else {
-#pragma unroll
-      for (int j = 0; j < kChunks; ++j) md[j] = zero_raw();
-      sd = 0.f;
-    }
+    for (int j = 0; j < kChunks; ++j) md[j] = load_raw_stream(row + j * (kE * kRowLanes), kNT);
+    sd = reinterpret_cast<const float*>(rec + std_off)[hkv];
   };
-  if (n_steps > 0) issue(0, mc, sd_cur, phys_cur);
-  for (int st = 0; st < n_steps; ++st) {
-    if (st + 1 < n_steps) issue(st + 1, mn, sd_nxt, phys_nxt);
+  auto consume = [&](int st, const Raw16(&mc)[kChunks], float sd_cur, int phys_cur) {
     float mf[kDot2 ? 1 : kChunks][kE];
     if constexpr (!kDot2) {
 #pragma unroll
@@ -261,17 +265,23 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     }
     const int p = tile0 + (wave_slot + st * wave_slots) * pages_per_step + page_in_step;
     // a page whose table entry points outside the pool gets NaN, which ranks below every score
-    if (cl == 0 && p < tile_end) tile_scores[hkv * kTilePages + p - tile0] = phys_cur >= 0 ? best : __uint_as_float(0x7fc00000u);
+    if (cl == 0 && p < tile_end) tile_scores[hkv * tile_pages + p - tile0] = phys_cur >= 0 ? best : __uint_as_float(0x7fc00000u);
+  };
 #pragma unroll
-    for (int j = 0; j < kChunks; ++j) mc[j] = mn[j];
-    sd_cur = sd_nxt;
-    phys_cur = phys_nxt;
+  for (int u = 0; u < kDepth; ++u) issue(u, ring[u], ring_sd[u], ring_phys[u]);
+  for (int st0 = 0; st0 < n_steps; st0 += kDepth) {
+#pragma unroll
+    for (int u = 0; u < kDepth; ++u) {
+      consume(st0 + u, ring[u], ring_sd[u], ring_phys[u]);
+      issue(st0 + u + kDepth, ring[u], ring_sd[u], ring_phys[u]);
+    }
   }
   __syncthreads();
   // the tile's scores leave as one contiguous run per KV head
   const int tile_len = tile_end - tile0;
-  for (int idx = threadIdx.x; idx < c.Hkv * kTilePages; idx += kScoreWaves * kWave) {
-    const int h = idx / kTilePages, pp = idx % kTilePages;
+  const int tshift = __ffs(tile_pages) - 1;  // the tile is a power of two
+  for (int idx = threadIdx.x; idx < c.Hkv * tile_pages; idx += kScoreWaves * kWave) {
+    const int h = idx >> tshift, pp = idx & (tile_pages - 1);
     if (pp < tile_len) {
       const float v = tile_scores[idx];
       scores[((int64_t)b * c.Hkv + h) * score_stride + tile0 + pp] = v;
@@ -283,16 +293,28 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
 template <typename T, int D, int G>
 hipError_t launch_t(const CacheView& cv, const void* q, float lambda, float* scores, int stride, float* out,
                     bool refresh_tail, hipStream_t st) {
-  CacheView c = cv;
-  c.stream_nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
-  dim3 grid((c.max_pages_hint + kTilePages - 1) / kTilePages, c.B), block(kScoreWaves * kWave);
-  const size_t lds = (size_t)c.Hkv * kTilePages * sizeof(float);
-  if (c.stats_bf16)
-    page_score_kernel<T, bf16_t, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                                 stride, out, refresh_tail);
-  else
-    page_score_kernel<T, float, D, G><<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores,
-                                                                stride, out, refresh_tail);
+  const CacheView& c = cv;
+  const bool nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
+  // Small tiles balance ragged batches and small launches over the 256 CUs; a launch with workgroups to
+  // spare takes larger ones (fewer prologues). A wave keeps the page ids of all its steps in its 64
+  // lanes, which caps the tile at 64 pages when one wave steps through all 32 heads of a page alone.
+  const int max_tile = c.Hkv == 32 ? 64 : 128;
+  int tile = 32;
+  while (tile < max_tile && (int64_t)c.B * ((c.max_pages_hint + 2 * tile - 1) / (2 * tile)) >= UNIQUE_SCORE_FAT_GRID)
+    tile *= 2;
+  dim3 grid((c.max_pages_hint + tile - 1) / tile, c.B), block(kScoreWaves * kWave);
+  const size_t lds = (size_t)c.Hkv * tile * sizeof(float);
+  auto go = [&](auto kernel) {
+    kernel<<<grid, block, lds, st>>>(c, reinterpret_cast<const T*>(q), lambda, scores, stride, out, refresh_tail,
+                                     tile);
+  };
+  if (c.stats_bf16) {
+    if (nt) go(page_score_kernel<T, bf16_t, D, G, true>);
+    else go(page_score_kernel<T, bf16_t, D, G, false>);
+  } else {
+    if (nt) go(page_score_kernel<T, float, D, G, true>);
+    else go(page_score_kernel<T, float, D, G, false>);
+  }
   return hipGetLastError();
 }
 

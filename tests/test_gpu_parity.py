@@ -372,6 +372,28 @@ def test_random_shape_sweep(gpu_lib, seed):
     assert torch.equal(keep[1].view(torch.uint8), sess.out.view(torch.uint8))
 
 
+@pytest.mark.parametrize("Hkv,width", [(8, 4096), (8, 8192), (16, 8192), (32, 8192)])
+def test_wide_page_tables_take_the_larger_score_tiles(gpu_lib, Hkv, width):
+    """The score kernel sizes its grid from the page-table width (no length hint given) and moves from 32-page
+    to 64- and 128-page tiles once that grid has workgroups to spare (64 sequences x 4096 / 8192 table entries
+    here; 32 KV heads stay at 64). The sequences are short and ragged, two of them span several tiles."""
+    import dataclasses
+    rng = np.random.default_rng(77 + Hkv + width)
+    B = 64
+    lens = [int(x) for x in np.exp(rng.uniform(np.log(1), np.log(600), size=B)).round().clip(1, 600)]
+    lens[3], lens[40] = 3000, 2049
+    wl = W.build("wide", 31, dtype=torch.bfloat16, B=B, H=2 * Hkv, Hkv=Hkv, D=64, S=16, seq_lens=lens, top_k=24,
+                 key_mode="shift", plant_mode="one_percent", permute=True).to(DEV)
+    wide = torch.zeros((B, width), dtype=torch.int32, device=wl.page_table.device)
+    wide[:, :wl.max_pages] = wl.page_table
+    wl = dataclasses.replace(wl, page_table=wide)
+    sess = DecodeSession(wl, max_seq_len_hint=0)
+    rows = [(b, h) for b in (0, 3, 40, 63) for h in sorted({0, Hkv // 2, Hkv - 1})]
+    say(f"Hkv={Hkv} width={width} rows={rows}")
+    sess, rep = Hn.full_check(wl, sess=sess, rows=rows)
+    say(rep)
+
+
 def test_sequence_length_hint_contract(gpu_lib):
     """max_seq_len_hint = 0 means the page-table width; a hint below the real length cuts the sequence at the
     hinted page count in every kernel (documented: the hint has to be a true upper bound)."""
