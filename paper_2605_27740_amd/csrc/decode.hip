@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
   if (begin >= cnt) return;
   const int end = min(begin + pages_per_split, cnt);
 
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int tr = lane / kLanesPerTok, ch = lane % kLanesPerTok;
 
   float qv[G][kVec];
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
 
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int row = b * c.Hkv + hkv;
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int begin = split * pages_per_split;
   // the first list entry of this lane is requested together with the lengths (row storage is sel_stride
   // entries long, so the load does not have to wait for the count)

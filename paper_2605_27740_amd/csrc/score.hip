@@ -59,7 +59,7 @@ __device__ __forceinline__ void refresh_tail_record(const CacheView& c, int b, i
   constexpr int kVec = Elem<T>::kVec;
   constexpr int kLanesPerTok = D / kVec;
   constexpr int kTokPerLoad = kWave / kLanesPerTok;
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int tr = lane / kLanesPerTok, ch = lane % kLanesPerTok;
   const int p = P - 1, S = c.S;
   const int n = min(S, N - p * S);
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
 
   const int b = blockIdx.y;
   const int tile0 = blockIdx.x * tile_pages;  // tile_pages logical pages per workgroup (32, 64 or 128)
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int row8 = lane / kRowLanes, cl = lane % kRowLanes;
   // which head and which page of a step this lane's row is; both fixed for the whole kernel
   int hkv, page_in_step, pages_per_step, wave_slot, wave_slots;
