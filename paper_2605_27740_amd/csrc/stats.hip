@@ -167,14 +167,23 @@ __global__ __launch_bounds__(kStatsWaves* kWave) void page_stats_kernel(CacheVie
     }
   };
 
-  // two register buffers: the next batch is requested before the current one is reduced
+  // Two register buffers: the next batch is requested before the current one is reduced. The steady-state
+  // loop has no branches (both following batches exist); the last one or two batches are peeled off.
   Raw16 buf_a[kItems][kLoads], buf_b[kItems][kLoads];
   load_batch(0, buf_a);
-  for (int t = 0; t < batches; t += 2) {
+  int t = 0;
+  for (; t + 2 < batches; t += 2) {
     load_batch(t + 1, buf_b);
     reduce_batch(t, buf_a);
     load_batch(t + 2, buf_a);
     reduce_batch(t + 1, buf_b);
+  }
+  if (t + 1 < batches) {
+    load_batch(t + 1, buf_b);
+    reduce_batch(t, buf_a);
+    reduce_batch(t + 1, buf_b);
+  } else {
+    reduce_batch(t, buf_a);
   }
 }
 
@@ -186,7 +195,9 @@ hipError_t dispatch_s(const CacheView& cv, const int32_t* tb, const int32_t* te,
   // the (power-of-two) head count: a wave owns whole pages, or an aligned group of heads of one page.
   auto launch = [&](auto kernel, int k_items) {
     const int64_t total = (int64_t)pages_per_seq * c.Hkv;
-    int64_t ipw = k_items;
+    // a launch with very few items (the tail-page refresh) gives every item its own wave; otherwise a wave
+    // takes at least one full batch
+    int64_t ipw = total * c.B <= 4096 ? 1 : k_items;
     while (ipw * UNIQUE_STATS_TARGET_WAVES < total * c.B && ipw < (int64_t)kStatsMaxPagesPerWave * c.Hkv) ipw *= 2;
     const int64_t waves = (total + ipw - 1) / ipw;
     const dim3 grid((unsigned)((waves + kStatsWaves - 1) / kStatsWaves), c.B), block(kStatsWaves * kWave);
