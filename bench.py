@@ -144,6 +144,19 @@ def main():
     torch.cuda.synchronize()
     other_us = start.elapsed_time(stop) / args.steps * 1e3
 
+    # --- the one-call step captured once into a HIP graph and replayed (the calls only launch kernels)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fused_step()
+    graph.replay()
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(args.steps):
+        graph.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    graph_us = start.elapsed_time(stop) / args.steps * 1e3
+
     # --- the same K steps again with an event between stages (stage breakdown; the events cost a little)
     # (score and select are launched through their own entry points here: the same two kernels as the fused call)
     stride = (wl.max_pages + 63) // 64 * 64
@@ -251,7 +264,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "storage_dtype": str(wl.dtype).replace("torch.", ""), "stats_dtype": args.stats_dtype,
         "data": "synthetic", "step_call": "separate calls" if args.separate_calls else "unique_decode_step",
-        "other_step_call_us": other_us,
+        "other_step_call_us": other_us, "step_graph_replay_us": graph_us,
         "config": {"workload": wl.name, "batch": wl.B, "q_heads": wl.H, "kv_heads": wl.Hkv, "head_dim": wl.D,
                    "page_size": wl.S, "context": max(seq_lens), "total_tokens": sum(seq_lens), "top_k_pages": sess.top_k,
                    "lambda": wl.lam},

@@ -421,6 +421,49 @@ def test_sequence_length_hint_contract(gpu_lib):
     assert torch.isfinite(short.page_std[used]).all() and (short.page_stats[rest] == 0xFF).all()
 
 
+def test_decode_step_replays_from_a_captured_graph(gpu_lib):
+    """The entry points only launch kernels (no allocation, no memset, no synchronisation), so a step can be
+    captured into a HIP graph once and replayed while the cache grows: every replay has to see the keys, values,
+    lengths and queries as they are at replay time. Replays are interleaved with eager work and synchronisations,
+    and each one is compared bit for bit with an eager call on the same state (and the last with the oracle)."""
+    wl = W.config4(batch=6, min_context=300, max_context=6000, top_k=8, spare_tokens=64).to(DEV)
+    sess = DecodeSession(wl)
+    sess.update_page_stats()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            sess.decode_step(refresh_tail=True)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sess.decode_step(refresh_tail=True)
+        sess.dense_paged_decode()
+    for step in range(12):
+        W.append_tokens(wl, step)
+        wl.q.copy_(torch.roll(wl.q, 1, dims=1))      # new queries in place
+        for t in (sess.sel_pages, sess.sel_count):
+            t.fill_(-5)
+        sess.out.zero_(); sess.lse.zero_(); sess.out_dense.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (sess.sel_pages, sess.sel_count, sess.out, sess.lse, sess.out_dense, sess.page_stats)]
+        sess.decode_step(refresh_tail=True)
+        sess.dense_paged_decode()
+        torch.cuda.synchronize()
+        want = (sess.sel_pages, sess.sel_count, sess.out, sess.lse, sess.out_dense, sess.page_stats)
+        for i, (a, b) in enumerate(zip(got, want)):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {step}: output {i} differs from the eager call"
+    oc, q = Hn.oracle_cache(wl)
+    sel, cnt = sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy()
+    for (b, hkv) in [(0, 0), (3, 2), (5, wl.Hkv - 1)]:
+        mean_o, std_o = Hn.check_stats_row(sess, oc, b, hkv)
+        s_o = oracle.page_scores(oc, q, b, hkv, wl.lam, mean_o, std_o)
+        Hn.check_selection_row(sel[b, hkv], int(cnt[b, hkv]), s_o, sess.top_k, f"row ({b},{hkv})")
+        Hn.check_attention_head(sess.out, sess.lse, oc, q, b, hkv * wl.G, sel[b, hkv, :cnt[b, hkv]], wl.dtype)
+
+
 def test_calls_on_a_side_stream(gpu_lib):
     """Every call enqueues on the stream it is given (here a non-default torch stream) and nowhere else."""
     wl = W.config3(batch=2, context=8192, top_k=32).to(DEV)
