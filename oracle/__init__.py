@@ -135,6 +135,24 @@ def topk(scores: np.ndarray, k: int):
     return order, int(kb)
 
 
+def topk_forced(scores: np.ndarray, k: int, force_recent: int):
+    """Selection with the always-keep option of the C ABI (a serving option, not part of the paper: Section 4.2
+    states that the method needs no local window, so force_recent = 0 is the paper's behaviour). The last
+    n = min(force_recent, k, P) logical pages are selected whatever their scores; the other min(k, P) - n places
+    go to the best of the remaining pages under the (score desc, index asc) ranking.
+    -> ascending int32 array of min(k, P) pages."""
+    scores = np.ascontiguousarray(scores, np.float64)
+    P = scores.shape[0]
+    kb = min(int(k), P)
+    n = min(int(force_recent), kb)
+    forced = np.arange(P - n, P, dtype=np.int64)
+    rest = np.zeros((0,), np.int64)
+    if kb - n > 0:
+        order, _ = topk(scores[:P - n], kb - n)
+        rest = order[:kb - n].astype(np.int64)
+    return np.sort(np.concatenate([rest, forced])).astype(np.int32)
+
+
 def attention(c: OracleCache, q: np.ndarray, b: int, h: int, pages, sm_scale: float = 0.0):
     """Eq. 5 over the given logical pages (Eq. 4 if they are all pages) -> (out [D], lse)."""
     c._check_q(q)

@@ -61,7 +61,7 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
   if ((uintptr_t)d->page_stats & 127u) return fail(UNIQUE_ERR_INVALID_ARG, "page_stats must be 128-byte aligned");
   if (d->stats_dtype != UNIQUE_DTYPE_F32 && d->stats_dtype != UNIQUE_DTYPE_BF16)
     return fail(UNIQUE_ERR_INVALID_ARG, "stats_dtype %d is neither fp32 (0) nor bf16 (1)", d->stats_dtype);
-  if (d->reserved != 0) return fail(UNIQUE_ERR_INVALID_ARG, "reserved field must be 0");
+  if (d->force_recent_pages < 0) return fail(UNIQUE_ERR_INVALID_ARG, "force_recent_pages must be >= 0");
   {
     const int64_t tile = (int64_t)d->page_size * d->head_dim;
     const int64_t hs = d->kv_head_stride ? d->kv_head_stride : tile;
@@ -84,6 +84,7 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
   v->B = d->batch;
   v->max_pages = d->max_pages_per_seq;
   v->num_phys = d->num_phys_pages;
+  v->force_recent = d->force_recent_pages;
   v->dtype = d->dtype;
   int hint_pages = d->max_pages_per_seq;
   if (d->max_seq_len_hint > 0) {

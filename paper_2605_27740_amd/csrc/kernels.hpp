@@ -21,6 +21,7 @@ struct CacheView {
   int32_t stream_nt;          // set per launch: read the streamed operand with non-temporal loads
   int64_t kv_page_stride;     // elements between consecutive physical pages of k_cache (and of v_cache)
   int64_t kv_head_stride;     // elements between consecutive KV heads inside a page
+  int32_t force_recent;       // the last this-many logical pages of a sequence are always selected (0: none)
 };
 
 // Launches that stream more than this many bytes bypass cache allocation (the Infinity Cache holds 256 MB).

@@ -21,6 +21,7 @@ namespace unique {
 namespace {
 
 constexpr int kMaxRankCandidates = 512;  // above this the boundary bucket is resolved by radix rounds
+constexpr uint32_t kKeyForced = 0xffffffffu;  // key of a page that is selected whatever its score
 
 template <int kThreads>
 __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long v,
@@ -131,6 +132,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
 
   const int first = t * kItems;
   const int nv = max(0, min(kItems, P - first));  // valid items of this thread
+  const int forced_from = P - min(c.force_recent, kb);  // pages from here on are always selected
 
   uint32_t key[kItems];
   if constexpr (kItems >= 4) {
@@ -145,6 +147,10 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
 #pragma unroll
     for (int j = 0; j < kItems; ++j) key[j] = j < nv ? float_to_ordered(srow[first + j]) : 0u;
   }
+  // an always-selected page takes the largest key there is (above +inf), so it outranks every score
+#pragma unroll
+  for (int j = 0; j < kItems; ++j)
+    if (first + j >= forced_from) key[j] = kKeyForced;
 
   // ---- 1. linear-bucket histogram between the row's smallest and largest finite score
   constexpr uint32_t kKeyNegInf = 0x007fffffu, kKeyPosInf = 0xff800000u;  // keys of -inf and +inf
@@ -289,7 +295,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_long_kernel(CacheView c,
   const int ipt = (P + kThreads - 1) / kThreads;
   const int first = t * ipt;
   const int nv = max(0, min(ipt, P - first));
-  auto key_at = [&](int j) { return float_to_ordered(srow[first + j]); };
+  const int forced_from = P - min(c.force_recent, kb);  // pages from here on are always selected
+  auto key_at = [&](int j) { return first + j >= forced_from ? kKeyForced : float_to_ordered(srow[first + j]); };
 
   int need = kb;
   const uint32_t T = radix_threshold<kThreads, 0>(nv, key_at, [&](int) { return true; }, need, hist, &s_prefix, &s_need);

@@ -11,7 +11,8 @@ from .workloads import Workload
 
 class DecodeSession:
     def __init__(self, wl: Workload, top_k: int | None = None, max_seq_len_hint: int | None = None,
-                 want_scores: bool = True, lib: binding.Library | None = None, stats_dtype=torch.float32):
+                 want_scores: bool = True, lib: binding.Library | None = None, stats_dtype=torch.float32,
+                 force_recent_pages: int = 0):
         assert wl.k_cache.is_cuda, "the workload must live on the GPU"
         self.lib = lib or binding.load()
         self.wl = wl
@@ -32,7 +33,8 @@ class DecodeSession:
         self.desc = binding.make_desc(q_heads=wl.H, k_cache=wl.k_cache, v_cache=wl.v_cache,
                                       page_stats=self.page_stats, stats_dtype=stats_dtype,
                                       page_table=wl.page_table, seq_lens=wl.seq_lens,
-                                      max_seq_len_hint=max_seq_len_hint)
+                                      max_seq_len_hint=max_seq_len_hint, force_recent_pages=force_recent_pages)
+        self.force_recent_pages = int(force_recent_pages)
         self.sel_pages = torch.full((wl.B, wl.Hkv, self.top_k), -7, device=dev, dtype=torch.int32)
         self.sel_count = torch.full((wl.B, wl.Hkv), -7, device=dev, dtype=torch.int32)
         self.scores = (torch.full((wl.B, wl.Hkv, wl.max_pages), float("nan"), device=dev, dtype=torch.float32)

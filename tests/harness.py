@@ -71,8 +71,9 @@ def check_scores_row(sess: DecodeSession, oc: OracleCache, q: np.ndarray, b: int
     return s_o
 
 
-def check_selection_row(sel_row: np.ndarray, count: int, s_o: np.ndarray, top_k: int, where=""):
-    """Near-tie-aware comparison of one row's selected set with the oracle ranking."""
+def check_selection_row(sel_row: np.ndarray, count: int, s_o: np.ndarray, top_k: int, where="", force_recent=0):
+    """Near-tie-aware comparison of one row's selected set with the oracle ranking. With force_recent = n the last
+    min(n, k, P) pages must be selected and the rest of the set is compared with the ranking of the other pages."""
     P = s_o.shape[0]
     kb = min(top_k, P)
     assert count == kb, f"{where}: sel_count {count} != min(k, P) = {kb}"
@@ -83,6 +84,13 @@ def check_selection_row(sel_row: np.ndarray, count: int, s_o: np.ndarray, top_k:
     if kb == P:
         assert T.tolist() == list(range(P))
         return True
+    if force_recent > 0:
+        n = min(force_recent, kb)
+        assert T[kb - n:].tolist() == list(range(P - n, P)), f"{where}: the last {n} pages are not all selected"
+        if kb == n:
+            return True
+        rest = np.concatenate([T[:kb - n], np.full((top_k - (kb - n),), -1, T.dtype)])
+        return check_selection_row(rest, kb - n, s_o[:P - n], top_k - n, where, 0)   # here kb = top_k < P
     order, _ = oracle.topk(s_o, top_k)
     s_k, s_k1 = s_o[order[kb - 1]], s_o[order[kb]]
     eps = 1e-4 * max(abs(s_k), abs(s_k1))
@@ -130,7 +138,8 @@ def full_check(wl: Workload, sess: DecodeSession | None = None, rows=None, dense
     for (b, hkv) in rows:
         mean_o, std_o = check_stats_row(sess, oc, b, hkv)
         s_o = check_scores_row(sess, oc, q, b, hkv, lam, mean_o, std_o)
-        n_exact += bool(check_selection_row(sel[b, hkv], int(cnt[b, hkv]), s_o, sess.top_k, f"row ({b},{hkv})"))
+        n_exact += bool(check_selection_row(sel[b, hkv], int(cnt[b, hkv]), s_o, sess.top_k, f"row ({b},{hkv})",
+                                            getattr(sess, "force_recent_pages", 0)))
         T = sel[b, hkv, :cnt[b, hkv]]
         for g in range(wl.G):
             h = hkv * wl.G + g

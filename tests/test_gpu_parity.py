@@ -182,13 +182,14 @@ def test_exact_ties_take_lowest_pages(gpu_lib):
     assert rep2["exact_sets"] == rep2["rows"]
 
 
-def _crafted_select(P, top_k, make_scores, S=8):
-    """Plant arbitrary fp32 scores: q = e_0 and mean[.., 0] = score, std = 0, so Eq. 3 returns them exactly."""
+def _crafted_select(P, top_k, make_scores, S=8, force_recent=0):
+    """Plant arbitrary fp32 scores: q = e_0 and mean[.., 0] = score, std = 0, so Eq. 3 returns them exactly.
+    force_recent = n: the last min(n, k, P) pages are expected whatever their scores, the rest from the other pages."""
     wl = W.build("crafted", 9, dtype=torch.float32, B=2, H=2, Hkv=2, D=64, S=S, seq_lens=[P * S, P * S - 3],
                  top_k=top_k, key_mode="iid", poison=False).to(DEV)
     wl.q.zero_()
     wl.q[..., 0] = 1.0
-    sess = DecodeSession(wl)
+    sess = DecodeSession(wl, force_recent_pages=force_recent)
     sess.page_stats.zero_()
     rows = {}
     for b in range(2):
@@ -202,16 +203,17 @@ def _crafted_select(P, top_k, make_scores, S=8):
     for (b, h), sc in rows.items():
         assert np.array_equal(got[b, h, :P], sc, equal_nan=True), "planted scores did not come back exactly"
         kb = min(top_k, P)
+        nf = min(force_recent, kb)
         nan = np.isnan(sc)
         key = np.where(nan, -np.inf, sc.astype(np.float64))
-        order = np.lexsort((np.arange(P), -key, nan))      # NaN last, then score descending, then page ascending
-        expect = np.sort(order[:kb])
+        free = P - nf                                        # pages that compete on their scores
+        order = np.lexsort((np.arange(free), -key[:free], nan[:free]))   # NaN last, score descending, page ascending
+        expect = np.sort(np.concatenate([order[:kb - nf], np.arange(free, P)]))
         assert cnt[b, h] == kb
-        assert np.array_equal(sel[b, h, :kb], expect), f"P={P} k={top_k} row ({b},{h})"
+        assert np.array_equal(sel[b, h, :kb], expect), f"P={P} k={top_k} forced={force_recent} row ({b},{h})"
         assert (sel[b, h, kb:] == -1).all()
         if not nan.any():                                   # the oracle's ranking agrees with numpy's
-            o, _ = oracle.topk(sc.astype(np.float64), top_k)
-            assert np.array_equal(np.sort(o[:kb]), expect)
+            assert np.array_equal(oracle.topk_forced(sc.astype(np.float64), top_k, force_recent), expect)
 
 
 SCORE_MAKERS = {
@@ -241,6 +243,34 @@ def test_select_exact_on_crafted_scores(gpu_lib, kind, P, top_k):
 def test_select_row_length_boundaries(gpu_lib, P):
     _crafted_select(P, 37, SCORE_MAKERS["heavy_ties"])
     _crafted_select(P, P - 1, SCORE_MAKERS["normal"])
+
+
+@pytest.mark.parametrize("kind", ["normal", "heavy_ties", "descending", "nan_and_inf", "all_equal"])
+@pytest.mark.parametrize("P,top_k", [(200, 16), (8192, 256), (40000, 64)])
+@pytest.mark.parametrize("n", [1, 3, "k", "k+5"])
+def test_forced_recent_pages_on_crafted_scores(gpu_lib, kind, P, top_k, n):
+    """force_recent_pages: the last pages are selected whatever they score (descending scores rank them last, NaN
+    scores rank below everything); n = k leaves no free place, n > k is cut to k."""
+    n = {"k": top_k, "k+5": top_k + 5}.get(n, n)
+    _crafted_select(P, top_k, SCORE_MAKERS[kind], force_recent=n)
+
+
+def test_forced_recent_pages_through_the_step_against_the_oracle(gpu_lib):
+    wl = W.config3(batch=2, context=6000 + 5, top_k=24).to(DEV)
+    sess = DecodeSession(wl, force_recent_pages=4)
+    sess, rep = Hn.full_check(wl, sess=sess)
+    say(rep)
+    P = wl.num_pages(0)
+    assert (sess.sel_pages[:, :, -4:].cpu() == torch.arange(P - 4, P)).all()
+    plain = DecodeSession(wl)
+    plain.update_page_stats()
+    plain.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    assert not torch.equal(plain.sel_pages, sess.sel_pages), "the planted workload should not pick the last 4 pages by itself"
+    keep = (sess.sel_pages.clone(), sess.out.clone())
+    sess.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    assert torch.equal(keep[0], sess.sel_pages) and torch.equal(keep[1].view(torch.uint8), sess.out.view(torch.uint8))
 
 
 def test_split_score_and_select_calls_match_the_fused_call(gpu_lib):

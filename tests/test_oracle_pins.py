@@ -476,3 +476,27 @@ def test_planted_keys_need_the_std_offset():
     rank_without = np.argsort(np.argsort(-s_without))[planted]
     assert rank_with.sum() <= rank_without.sum()
     assert (rank_with < wl.top_k).all()
+
+
+def test_topk_forced_recent_pages_invariants():
+    """The always-keep option (C ABI; not from the paper, whose method needs no local window -- Section 4.2):
+    the set has min(k, P) pages, contains the last min(n, k, P), and among the other pages every selected one
+    outranks every unselected one under (score desc, index asc); n = 0 is the plain top-k."""
+    rng = np.random.default_rng(5)
+    for trial in range(300):
+        P = int(rng.integers(1, 40))
+        k = int(rng.integers(1, 45))
+        n = int(rng.integers(0, 12))
+        s = rng.integers(-3, 4, size=P).astype(np.float64) if trial % 2 else rng.normal(size=P)
+        got = oracle.topk_forced(s, k, n)
+        kb, nf = min(k, P), min(n, k, P)
+        assert got.shape == (kb,) and (np.diff(got) > 0).all()
+        assert set(range(P - nf, P)) <= set(got.tolist())
+        if n == 0:
+            order, _ = oracle.topk(s, k)
+            assert sorted(order[:kb].tolist()) == got.tolist()
+        chosen = [p for p in got.tolist() if p < P - nf]
+        others = [p for p in range(P - nf) if p not in chosen]
+        for a in chosen:
+            for b in others:
+                assert (s[a], -a) > (s[b], -b), (trial, a, b)
