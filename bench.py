@@ -317,6 +317,24 @@ def paper_shapes(dev):
             row[f"score_us_{name}"] = median_us(lambda: sess.page_scores(buf), 100, 20)
             stat_bytes = wl.B * P * sess.page_stats.shape[1]
             row[f"score_GBps_{name}"] = stat_bytes / row[f"score_us_{name}"] / 1e3
+            if sd == torch.bfloat16:
+                # Ablation (Appendix A's unfused baseline): the same scores from library launches on a contiguous,
+                # already gathered copy of the statistics -- a batched GEMM q . mean^T that writes the [B, H, P]
+                # intermediate, the rank-one offset, the max over the group. Not part of the product path.
+                ptl = wl.page_table[:, :P].long()
+                means_c = sess.page_mean[ptl].permute(0, 2, 1, 3).contiguous()        # [B, Hkv, P, D] bf16
+                stds_c = sess.page_std[ptl].permute(0, 2, 1).contiguous()             # [B, Hkv, P] fp32
+                qg = wl.q.view(wl.B, wl.Hkv, wl.G, wl.D)
+                off = (wl.lam * qg.float().norm(dim=-1)).unsqueeze(-1)                # [B, Hkv, G, 1]
+                def naive():
+                    dots = torch.matmul(qg, means_c.transpose(-1, -2)).float()        # [B, Hkv, G, P]
+                    dots.addcmul_(off, stds_c.unsqueeze(2))
+                    return dots.amax(dim=2)
+                row["naive_library_launches_us_bf16_stats"] = median_us(naive, 100, 20)
+                ref = naive()
+                sess.page_scores(buf)
+                row["naive_max_abs_diff"] = float((ref - buf[:, :, :P]).abs().max())
+                del means_c, stds_c, ref
             if sd == torch.float32:
                 row["topk_us"] = median_us(lambda: sess.select_topk(buf), 300, 50)
                 # Fig. 2 of the paper: attention over a 512-token budget (k = 64 pages of 8) vs dense
