@@ -26,11 +26,22 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// With a single chunk per row there is nothing to merge: the partial kernel writes the attention output
+// itself, with the arithmetic of the merge kernel (a scale of exp2(0) = 1), so the result is the same bits.
+template <typename T>
+__device__ __forceinline__ void write_final(const CacheView& c, T* out, float* lse_out, int b, int h, int d, int D,
+                                            float o, float M, float L) {
+  const bool any = L > 0.f;
+  store_elem(out + ((int64_t)b * c.H + h) * D + d, any ? o / L : 0.f);
+  if (lse_out && d == 0) lse_out[(int64_t)b * c.H + h] = any ? (M + log2f(L)) * kLn2 : -INFINITY;
+}
+
 template <typename T, int D, int S, int G>
 __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
     CacheView c, const T* __restrict__ q, const int32_t* __restrict__ sel_pages,
     const int32_t* __restrict__ sel_count, int sel_stride, int pages_per_split, int num_splits, float scale_log2,
-    float* __restrict__ part_o /*[rows][num_splits][G][D]*/, float* __restrict__ part_ml /*[rows][num_splits][G][2]*/) {
+    float* __restrict__ part_o /*[rows][num_splits][G][D]*/, float* __restrict__ part_ml /*[rows][num_splits][G][2]*/,
+    T* __restrict__ out, float* __restrict__ lse_out /* written directly when num_splits == 1 */) {
   constexpr int kVec = Elem<T>::kVec;
   constexpr int kLanesPerTok = D / kVec;
   constexpr int kTokPerLoad = kWave / kLanesPerTok;
@@ -45,7 +56,13 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
   const int P = min((N + S - 1) / S, c.max_pages_hint);
   const int cnt = sel_pages ? min(sel_count[row], sel_stride) : P;
   const int begin = split * pages_per_split;
-  if (begin >= cnt) return;
+  if (begin >= cnt) {
+    if (num_splits == 1) {  // an empty list: the output is defined as zero, the lse as -inf
+      for (int idx = threadIdx.x; idx < G * D; idx += kDecWaves * kWave)
+        write_final(c, out, lse_out, b, hkv * G + idx / D, idx % D, D, 0.f, 0.f, 0.f);
+    }
+    return;
+  }
   const int end = min(begin + pages_per_split, cnt);
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
@@ -207,10 +224,14 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
       o = fmaf(sm_acc[w][g][d], sc, o);
       L = fmaf(sm_l[w][g], sc, L);
     }
-    part_o[(pbase * G + g) * D + d] = o;
-    if (d == 0) {
-      part_ml[(pbase * G + g) * 2 + 0] = M;
-      part_ml[(pbase * G + g) * 2 + 1] = L;
+    if (num_splits == 1) {
+      write_final(c, out, lse_out, b, hkv * G + g, d, D, o, M, L);
+    } else {
+      part_o[(pbase * G + g) * D + d] = o;
+      if (d == 0) {
+        part_ml[(pbase * G + g) * 2 + 0] = M;
+        part_ml[(pbase * G + g) * 2 + 1] = L;
+      }
     }
   }
 }
@@ -239,7 +260,7 @@ template <int D, int S, int G>
 __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_kernel(
     CacheView c, const bf16_t* __restrict__ q, const int32_t* __restrict__ sel_pages,
     const int32_t* __restrict__ sel_count, int sel_stride, int pages_per_split, int num_splits, float scale_log2,
-    float* __restrict__ part_o, float* __restrict__ part_ml) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, bf16_t* __restrict__ out, float* __restrict__ lse_out) {
   constexpr int kVec = 8;
   constexpr int kTile = 16;                          // token slots per MFMA tile
   constexpr int kSteps = D / 32;                     // MFMA steps (and K loads per lane) per tile
@@ -264,7 +285,13 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
   const int N = c.seq_lens[b];
   const int P = min((N + S - 1) / S, c.max_pages_hint);
   const int cnt = sel_pages ? min(sel_count[row], sel_stride) : P;
-  if (begin >= cnt) return;
+  if (begin >= cnt) {
+    if (num_splits == 1) {  // an empty list: the output is defined as zero, the lse as -inf
+      for (int idx = threadIdx.x; idx < G * D; idx += kDecWaves * kWave)
+        write_final(c, out, lse_out, b, hkv * G + idx / D, idx % D, D, 0.f, 0.f, 0.f);
+    }
+    return;
+  }
   const int end = min(begin + pages_per_split, cnt);
 
   const int kt = lane % 16, kg = lane / 16;                       // K / logit layout: token slot, lane group
@@ -445,10 +472,14 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       o = fmaf(sm_acc[w][g][d], sc, o);
       L = fmaf(sm_l[w][g], sc, L);
     }
-    part_o[(pbase * G + g) * D + d] = o;
-    if (d == 0) {
-      part_ml[(pbase * G + g) * 2 + 0] = M;
-      part_ml[(pbase * G + g) * 2 + 1] = L;
+    if (num_splits == 1) {
+      write_final(c, out, lse_out, b, hkv * G + g, d, D, o, M, L);
+    } else {
+      part_o[(pbase * G + g) * D + d] = o;
+      if (d == 0) {
+        part_ml[(pbase * G + g) * 2 + 0] = M;
+        part_ml[(pbase * G + g) * 2 + 1] = L;
+      }
     }
   }
 }
@@ -495,14 +526,14 @@ hipError_t launch_t(const CacheView& cv, const void* q, const int32_t* sel, cons
   if constexpr (sizeof(T) == 2)
     paged_decode_partial_mfma_kernel<D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
         c, reinterpret_cast<const bf16_t*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
-        part_o, part_ml);
+        part_o, part_ml, reinterpret_cast<bf16_t*>(out), lse);
   else
 #endif
     paged_decode_partial_kernel<T, D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
         c, reinterpret_cast<const T*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
-        part_o, part_ml);
+        part_o, part_ml, reinterpret_cast<T*>(out), lse);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || plan.num_splits == 1) return e;  // one chunk per row: the partial kernel wrote the output
   paged_decode_merge_kernel<T, D, G><<<dim3(c.H, c.B), dim3(D), 0, st>>>(
       c, cnt, sel_stride, sel == nullptr, plan.pages_per_split, plan.num_splits, part_o, part_ml,
       reinterpret_cast<T*>(out), lse);

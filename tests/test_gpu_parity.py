@@ -542,6 +542,35 @@ def test_invalid_list_entries_are_skipped(gpu_lib):
     assert (sess.out == 0).all() and torch.isinf(sess.lse).all() and (sess.lse < 0).all()
 
 
+@pytest.mark.parametrize("list_len", [6, 700])
+def test_empty_and_all_invalid_lists_bf16(gpu_lib, list_len):
+    """bf16 caches (matrix-core kernel), a list short enough for one chunk per row (the partial kernel writes the
+    output itself) and one long enough for many chunks (merge kernel): rows with no entries, or with only invalid
+    entries, give zeros and lse = -inf; the other rows are unaffected."""
+    wl = W.config3(batch=2, context=16 * 900 + 5, top_k=16).to(DEV)
+    sess = DecodeSession(wl, top_k=list_len)      # sizes the workspace for lists of this length
+    rng = np.random.default_rng(list_len)
+    P = wl.num_pages(0)
+    sel_np = np.stack([np.sort(rng.choice(P, size=list_len, replace=False)) for _ in range(wl.B * wl.Hkv)])
+    sel = torch.from_numpy(sel_np.astype(np.int32)).view(wl.B, wl.Hkv, list_len).to(DEV)
+    cnt = torch.full((wl.B, wl.Hkv), list_len, device=DEV, dtype=torch.int32)
+    cnt[0, 1] = 0                       # empty list
+    sel[1, 2] = -1                      # only invalid entries
+    sel[1, 3, ::2] = 10 ** 6
+    sel[1, 3, 1::2] = -4
+    sess.out.fill_(7.0)
+    sess.lse.fill_(7.0)
+    sess.sparse_paged_decode(sel_pages=sel, sel_count=cnt)
+    torch.cuda.synchronize()
+    oc, q = Hn.oracle_cache(wl)
+    for (b, hkv) in [(0, 1), (1, 2), (1, 3)]:
+        hs = slice(hkv * wl.G, (hkv + 1) * wl.G)
+        assert (sess.out[b, hs] == 0).all() and (sess.lse[b, hs] == float("-inf")).all()
+    for (b, hkv) in [(0, 0), (0, 2), (1, 7)]:
+        for g in (0, wl.G - 1):
+            Hn.check_attention_head(sess.out, sess.lse, oc, q, b, hkv * wl.G + g, sel[b, hkv].cpu().numpy(), wl.dtype)
+
+
 def test_explicit_sm_scale(gpu_lib):
     wl = W.config1().to(DEV)
     sess = DecodeSession(wl)
