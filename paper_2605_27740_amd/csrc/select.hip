@@ -36,7 +36,11 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
   if (lane == kWave - 1) wave_tot[wave] = inc;
   __syncthreads();
   unsigned long long base = 0;
-  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+#pragma unroll
+  for (int w = 0; w < kThreads / kWave; ++w) {  // all totals are read at once, not one dependent read per wave
+    const unsigned long long tot = wave_tot[w];
+    base += w < wave ? tot : 0ull;
+  }
   return base + inc - v;
 }
 
