@@ -340,7 +340,7 @@ hipError_t launch_select(const CacheView& c, const float* d_scores, int score_st
   const int P = c.max_pages_hint;
   if (P <= 256) return launch_t<256, 1>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 1024) return launch_t<256, 4>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
-  if (P <= 2048) return launch_t<256, 8>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
+  if (P <= 2048) return launch_t<512, 4>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 4096) return launch_t<1024, 4>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 8192) return launch_t<1024, 8>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 16384) return launch_t<1024, 16>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
