@@ -45,6 +45,8 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
     return fail(UNIQUE_ERR_UNSUPPORTED, "batch and num_kv_heads are limited to 65535 (grid extent)");
   if ((int64_t)d->max_pages_per_seq * d->page_size > (int64_t)INT32_MAX)
     return fail(UNIQUE_ERR_INVALID_ARG, "max_pages_per_seq * page_size overflows int32 token positions");
+  if ((int64_t)d->max_pages_per_seq * d->num_kv_heads > (int64_t)INT32_MAX)
+    return fail(UNIQUE_ERR_UNSUPPORTED, "max_pages_per_seq * num_kv_heads overflows int32 (page, head) item indices");
   const int G = d->num_q_heads / d->num_kv_heads;
   if (!unique::stats_supported(d->dtype, d->head_dim, d->page_size) ||
       !unique::score_supported(d->dtype, d->head_dim, G, d->num_kv_heads) ||

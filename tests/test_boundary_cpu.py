@@ -69,6 +69,7 @@ def test_workspace_bytes(lib):
     (dict(max_seq_len_hint=-1), binding.ERR_INVALID_ARG),
     (dict(stats_dtype=3), binding.ERR_INVALID_ARG),
     (dict(force_recent_pages=-1), binding.ERR_INVALID_ARG),
+    (dict(max_pages_per_seq=2 ** 27, page_size=8, num_q_heads=32, num_kv_heads=32), binding.ERR_UNSUPPORTED),  # item index overflow
     (dict(page_stats=0x3010), binding.ERR_INVALID_ARG),       # needs 128-byte alignment
     (dict(kv_head_stride=1024), binding.ERR_INVALID_ARG),     # smaller than one S*D tile (2048)
     (dict(kv_head_stride=4096, kv_page_stride=4096 * 7), binding.ERR_INVALID_ARG),  # pages would overlap
