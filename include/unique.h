@@ -14,7 +14,9 @@
  *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and returns without synchronising. Buffers must stay
  *     alive, and must not be written by the caller, until the stream has reached
- *     that point.
+ *     that point. Nothing else happens on the stream (no allocation, memset, copy or wait), so
+ *     a sequence of calls may be captured into a HIP graph and replayed; grid sizes come from
+ *     the host-visible bounds in the descriptor, the device arrays are read at replay time.
  *   - Return value: UNIQUE_OK or an error code; unique_last_error() gives a
  *     thread-local description of the last failure. Host-visible arguments are
  *     validated before anything touches the device. The CONTENTS of device arrays
@@ -122,7 +124,7 @@ int unique_update_page_stats(const unique_cache_desc* desc, const int32_t* d_tok
  * each (sequence, KV head) (Section 3.2, radix selection; ties go to the lower logical page).
  *   d_q          : [batch][H][D] dtype.
  *   top_k >= 1   : pages to keep; each row keeps k_b = min(top_k, pages of the sequence). No page
- *                  is kept unconditionally.
+ *                  is kept unconditionally unless desc->force_recent_pages asks for it.
  *   lambda >= 0  : weight of the standard-deviation offset (0.5 in the paper).
  *   d_sel_pages  : out, int32 [batch][H_kv][top_k], LOGICAL page indices in ascending order,
  *                  entries at and beyond k_b are -1.
