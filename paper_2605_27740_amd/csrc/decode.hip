@@ -8,7 +8,8 @@
 // operations, and each group of lanes that shares a token row keeps its own online-softmax state, so
 // the inner loop has no cross-row communication. States are merged (log-sum-exp) across lane groups,
 // then across the 4 waves through LDS, and the chunk's partial (o, m, l) goes to the workspace; a
-// second small kernel merges the chunks of a row and writes the output in the cache dtype.
+// second small kernel merges the chunks of a row and writes the output in the cache dtype (a row with
+// a single chunk is written by the first kernel itself and the second is not launched).
 // Logits are kept in the log2 domain (q is pre-multiplied by sm_scale * log2 e) so exp is one v_exp_f32.
 #include "device_utils.hpp"
 #include "kernels.hpp"
