@@ -19,7 +19,7 @@ namespace {
 constexpr int kStatsWaves = 4;
 constexpr int kStatsMaxPagesPerWave = 32;  // <= wavefront size: lane l keeps the id of the wave's l-th page
 #ifndef UNIQUE_STATS_TARGET_WAVES
-#define UNIQUE_STATS_TARGET_WAVES 16384
+#define UNIQUE_STATS_TARGET_WAVES 65536
 #endif
 
 // (page, head) items per batch: about 8 16-byte loads per lane and batch; two batches are in flight per
