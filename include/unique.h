@@ -100,7 +100,8 @@ typedef struct unique_cache_desc {
 
 /* Bytes of device workspace that any of the calls below may need for this descriptor and top_k
  * (score rows, split-K partial results). Pass a buffer at least this large, 256-byte aligned.
- * The contents need no initialisation and carry nothing between calls. */
+ * The contents need no initialisation and carry nothing between calls; calls that may overlap in time
+ * (different streams) need a workspace each. */
 int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t* out_bytes);
 
 /* Bytes per page record of page_stats for this descriptor (see the layout above); 0 if desc is NULL or
