@@ -157,6 +157,22 @@ def main():
     torch.cuda.synchronize()
     graph_us = start.elapsed_time(stop) / args.steps * 1e3
 
+    # --- the same K steps with the other statistics format (bf16 means are the paper's storage format and half the
+    # bytes of the score stage; fp32 means give a selection that equals an exact fp32 ranking). Reported, not `value`.
+    other_dtype = torch.float32 if stats_dtype == torch.bfloat16 else torch.bfloat16
+    alt = DecodeSession(wl, want_scores=False, stats_dtype=other_dtype)
+    alt.update_page_stats()
+    for _ in range(args.warmup):
+        alt.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(args.steps):
+        alt.decode_step(refresh_tail=True)
+    stop.record()
+    torch.cuda.synchronize()
+    alt_us = start.elapsed_time(stop) / args.steps * 1e3
+    del alt
+
     # --- the same K steps again with an event between stages (stage breakdown; the events cost a little)
     # (score and select are launched through their own entry points here: the same two kernels as the fused call)
     stride = (wl.max_pages + 63) // 64 * 64
@@ -265,6 +281,7 @@ def main():
         "dtype": "f32", "storage_dtype": str(wl.dtype).replace("torch.", ""), "stats_dtype": args.stats_dtype,
         "data": "synthetic", "step_call": "separate calls" if args.separate_calls else "unique_decode_step",
         "other_step_call_us": other_us, "step_graph_replay_us": graph_us,
+        "other_stats_format": {"stats_dtype": "fp32" if other_dtype == torch.float32 else "bf16", "us_per_step": alt_us},
         "config": {"workload": wl.name, "batch": wl.B, "q_heads": wl.H, "kv_heads": wl.Hkv, "head_dim": wl.D,
                    "page_size": wl.S, "context": max(seq_lens), "total_tokens": sum(seq_lens), "top_k_pages": sess.top_k,
                    "lambda": wl.lam},
