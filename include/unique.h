@@ -37,7 +37,9 @@
  *                      read or written. The base pointer must be 128-byte aligned.
  *   page_table       : [batch][max_pages_per_seq]  int32, logical page -> physical page
  *   seq_lens         : [batch] int32, tokens cached per sequence INCLUDING the token being
- *                      decoded (the caller appends k_t, v_t first); must be >= 1
+ *                      decoded (the caller appends k_t, v_t first). 0 is tolerated: nothing of that
+ *                      sequence is read or refreshed, its rows select nothing (count 0) and its
+ *                      output rows are zero with lse = -inf
  *   q, out           : [batch][num_q_heads][head_dim] dtype; query head h uses KV head
  *                      h / (num_q_heads / num_kv_heads)
  *   Logical page p of sequence b holds tokens [p*S, min((p+1)*S, seq_lens[b])); only the

@@ -571,6 +571,29 @@ def test_empty_and_all_invalid_lists_bf16(gpu_lib, list_len):
             Hn.check_attention_head(sess.out, sess.lse, oc, q, b, hkv * wl.G + g, sel[b, hkv].cpu().numpy(), wl.dtype)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_a_sequence_of_length_zero_is_tolerated(gpu_lib, dtype):
+    """seq_lens[b] = 0 (documented as tolerated): no statistics record of that sequence is written, its rows select
+    nothing (count 0, -1 padding), its outputs are zero with lse = -inf, and the other sequences are unaffected."""
+    wl = W.build("zero_len", 43, dtype=dtype, B=3, H=8, Hkv=2, D=64, S=16, seq_lens=[700, 90, 333], top_k=6,
+                 key_mode="shift", plant_mode="one_percent", permute=True).to(DEV)
+    wl.seq_lens[1] = 0
+    sess = DecodeSession(wl)
+    sess.out.fill_(3.0); sess.lse.fill_(3.0); sess.out_dense.fill_(3.0); sess.lse_dense.fill_(3.0)
+    _, rep = Hn.full_check(wl, sess=sess, rows=[(0, 0), (0, 1), (2, 0), (2, 1)])
+    say(rep)
+    assert (sess.sel_count[1] == 0).all() and (sess.sel_pages[1] == -1).all()
+    for o, l in ((sess.out, sess.lse), (sess.out_dense, sess.lse_dense)):
+        assert (o[1] == 0).all() and (l[1] == float("-inf")).all()
+    pages_of_1 = wl.page_table[1, :6].long()
+    assert (sess.page_stats[pages_of_1] == 0xFF).all(), "a record of the empty sequence was written"
+    sess.sel_pages.fill_(-3)
+    sess.out.fill_(5.0)
+    sess.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    assert (sess.sel_count[1] == 0).all() and (sess.sel_pages[1] == -1).all() and (sess.out[1] == 0).all()
+
+
 def test_explicit_sm_scale(gpu_lib):
     wl = W.config1().to(DEV)
     sess = DecodeSession(wl)
