@@ -22,6 +22,7 @@ namespace {
 
 constexpr int kMaxRankCandidates = 512;  // above this the boundary bucket is resolved by radix rounds
 constexpr uint32_t kKeyForced = 0xffffffffu;  // key of a page that is selected whatever its score
+constexpr uint32_t kKeyNegInf = 0x007fffffu, kKeyPosInf = 0xff800000u;  // keys of -inf and +inf
 
 template <int kThreads>
 __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long v,
@@ -48,6 +49,15 @@ __device__ __forceinline__ float ordered_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// Bucket of a key in a histogram of n_buckets buckets that is linear in the score between lo and the row
+// maximum (scale = (n_buckets - 1) / range): monotone in the score, so bucket order never contradicts
+// score order. -inf and NaN go to the lowest bucket, +inf and always-selected pages to the highest.
+__device__ __forceinline__ int linear_bucket(uint32_t k, float lo, float scale, int n_buckets) {
+  if (k >= kKeyPosInf) return n_buckets - 1;
+  if (k > kKeyNegInf) return min(n_buckets - 1, max(0, (int)((ordered_to_float(k) - lo) * scale)));
+  return 0;
+}
+
 // One round-set of 8-bit radix selection over the keys accepted by `keep(j)`: returns the exact key of
 // the need-th largest accepted key and leaves in `need` how many keys equal to it must be taken.
 // hist: 256 ints of LDS; s_prefix / s_need: LDS scalars. All threads of the workgroup must call it.
@@ -64,11 +74,26 @@ __device__ __forceinline__ uint32_t radix_threshold(int n_items, KeyAt key_at, K
     __syncthreads();  // everyone is done with the previous contents of hist
     if (t < 256) hist[t] = 0;
     __syncthreads();
+    if constexpr (kStatic > 0) {
 #pragma unroll
-    for (int j = 0; j < n; ++j) {
-      if (keep(j)) {
-        const uint32_t k = key_at(j);
-        if (round == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+      for (int j = 0; j < n; ++j) {
+        if (keep(j)) {
+          const uint32_t k = key_at(j);
+          if (round == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+      }
+    } else {  // keys come from memory: eight reads are requested before the first one is used
+      for (int j0 = 0; j0 < n; j0 += 8) {
+        uint32_t kk[8];
+        bool kp[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          kp[u] = j0 + u < n && keep(j0 + u);
+          kk[u] = kp[u] ? key_at(j0 + u) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (kp[u] && (round == 0 || (kk[u] >> (shift + 8)) == prefix)) atomicAdd(&hist[(kk[u] >> shift) & 255u], 1);
       }
     }
     __syncthreads();
@@ -157,7 +182,6 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
     if (first + j >= forced_from) key[j] = kKeyForced;
 
   // ---- 1. linear-bucket histogram between the row's smallest and largest finite score
-  constexpr uint32_t kKeyNegInf = 0x007fffffu, kKeyPosInf = 0xff800000u;  // keys of -inf and +inf
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
@@ -181,21 +205,23 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
     if (range > 0.f && range < 3.0e38f) scale = (float)(kBuckets - 1) / range;
     if (!(scale < 3.0e38f)) scale = 0.f;  // a denormal range: leave everything in one bucket
   }
-  int bucket[kItems];
+  // the bucket of every key is kept in registers, unless the keys alone already take most of them
+  constexpr bool kKeepBuckets = kItems <= 32;
+  int bucket_reg[kKeepBuckets ? kItems : 1];
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
-    int bk = 0;
     if (j < nv) {
-      const uint32_t k = key[j];
-      if (k >= kKeyPosInf) bk = kBuckets - 1;  // +inf
-      else if (k > kKeyNegInf) {                // finite: monotone in the score
-        const float x = (ordered_to_float(k) - lo) * scale;
-        bk = min(kBuckets - 1, max(0, (int)x));
-      }                                         // -inf and NaN stay in bucket 0
+      const int bk = linear_bucket(key[j], lo, scale, kBuckets);
       atomicAdd(&hist[bk], 1);
+      if constexpr (kKeepBuckets) bucket_reg[j] = bk;
+    } else if constexpr (kKeepBuckets) {
+      bucket_reg[j] = 0;
     }
-    bucket[j] = bk;
   }
+  auto bucket = [&](int j) {
+    if constexpr (kKeepBuckets) return bucket_reg[j];
+    else return linear_bucket(key[j], lo, scale, kBuckets);
+  };
   __syncthreads();
   {  // suffix scan over the buckets: thread t owns buckets kBuckets-1-2t and kBuckets-2-2t
     const int c_hi = hist[kBuckets - 1 - 2 * t], c_lo = hist[kBuckets - 2 - 2 * t];
@@ -214,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
   if (ncand <= kMaxRank) {
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
-      if (j < nv && bucket[j] == bstar) {
+      if (j < nv && bucket(j) == bstar) {
         const int slot = atomicAdd(&s_ncand, 1);
         cand_key[slot] = key[j];
         cand_idx[slot] = first + j;
@@ -237,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
     need = s_need;
   } else {
     T = radix_threshold<kThreads, kItems>(
-        kItems, [&](int j) { return key[j]; }, [&](int j) { return j < nv && bucket[j] == bstar; }, need, hist,
+        kItems, [&](int j) { return key[j]; }, [&](int j) { return j < nv && bucket(j) == bstar; }, need, hist,
         &s_prefix, &s_need);
   }
 
@@ -246,8 +272,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     if (j < nv) {
-      const bool in_b = bucket[j] == bstar;
-      sure += (bucket[j] > bstar) || (in_b && key[j] > T);
+      const bool in_b = bucket(j) == bstar;
+      sure += (bucket(j) > bstar) || (in_b && key[j] > T);
       tie += in_b && key[j] == T;
     }
   }
@@ -257,8 +283,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     if (j < nv) {
-      const bool in_b = bucket[j] == bstar;
-      if ((bucket[j] > bstar) || (in_b && key[j] > T)) {
+      const bool in_b = bucket(j) == bstar;
+      if ((bucket(j) > bstar) || (in_b && key[j] > T)) {
         out[sure_b + min(tie_b, need)] = first + j;
         ++sure_b;
       } else if (in_b && key[j] == T) {
@@ -269,24 +295,35 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
   }
 }
 
-// Rows too long for registers: every pass re-reads the scores (they stay in L2). Plain four-round
-// radix selection over the 32-bit keys, then the same index-ordered compaction.
+// Rows too long for registers: the same three steps as above, but every pass re-reads the scores (they
+// stay in L2). Thread t owns the pages t, t + threads, t + 2*threads, ... so that every read of the row is
+// coalesced, and reads are requested eight at a time. The compaction walks the row in blocks of `threads`
+// consecutive pages and places each selected page by a ballot prefix inside its wave, the wave totals of
+// the block (LDS) and the running totals of the blocks before it, which keeps the output in ascending page
+// order and takes keys tied with the k-th from the lowest page upward.
 template <int kThreads>
 __global__ __launch_bounds__(kThreads) void topk_select_long_kernel(CacheView c, const float* __restrict__ scores,
                                                                     int score_stride, int top_k,
                                                                     int32_t* __restrict__ sel_pages,
                                                                     int32_t* __restrict__ sel_count) {
-  __shared__ int hist[256];
-  __shared__ unsigned long long wave_tot[kThreads / kWave];
+  constexpr int kWaves = kThreads / kWave;
+  constexpr int kBuckets = 2 * kThreads;
+  constexpr int kMaxRank = kThreads < kMaxRankCandidates ? kThreads : kMaxRankCandidates;
+  __shared__ int hist[kBuckets];
+  __shared__ unsigned long long wave_tot[kWaves];
+  __shared__ uint32_t wave_min[kWaves], wave_max[kWaves];
+  __shared__ uint32_t cand_key[kMaxRank];
+  __shared__ int cand_idx[kMaxRank];
+  __shared__ int wave_gt[2][kWaves], wave_eq[2][kWaves];
+  __shared__ int s_bucket, s_need, s_ncand;
   __shared__ uint32_t s_prefix;
-  __shared__ int s_need;
 
   const int row = blockIdx.x;
   const int b = row / c.Hkv;
   const int N = c.seq_lens[b];
   const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);
   const int kb = min(top_k, P);
-  const int t = threadIdx.x;
+  const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
   int32_t* out = sel_pages + (int64_t)row * top_k;
   const float* srow = scores + (int64_t)row * score_stride;
 
@@ -296,32 +333,129 @@ __global__ __launch_bounds__(kThreads) void topk_select_long_kernel(CacheView c,
     for (int i = t; i < P; i += kThreads) out[i] = i;
     return;
   }
-  const int ipt = (P + kThreads - 1) / kThreads;
-  const int first = t * ipt;
-  const int nv = max(0, min(ipt, P - first));
   const int forced_from = P - min(c.force_recent, kb);  // pages from here on are always selected
-  auto key_at = [&](int j) { return first + j >= forced_from ? kKeyForced : float_to_ordered(srow[first + j]); };
+  auto key_of = [&](int page) { return page >= forced_from ? kKeyForced : float_to_ordered(srow[page]); };
+  const int ipt = (P + kThreads - 1) / kThreads;  // strided items per thread; the last ones may fall past P
+  auto for_each_key = [&](auto f) {               // f(page, key) for every page this thread owns
+    for (int j0 = 0; j0 < ipt; j0 += 8) {
+      uint32_t kk[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int page = (j0 + u) * kThreads + t;
+        kk[u] = page < P ? key_of(page) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int page = (j0 + u) * kThreads + t;
+        if (page < P) f(page, kk[u]);
+      }
+    }
+  };
 
-  int need = kb;
-  const uint32_t T = radix_threshold<kThreads, 0>(nv, key_at, [&](int) { return true; }, need, hist, &s_prefix, &s_need);
-
-  uint32_t gt = 0, eq = 0;
-  for (int j = 0; j < nv; ++j) {
-    const uint32_t k = key_at(j);
-    gt += k > T;
-    eq += k == T;
+  // ---- 1. linear-bucket histogram between the row's smallest and largest finite score
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  for_each_key([&](int, uint32_t k) {
+    if (k > kKeyNegInf && k < kKeyPosInf) { kmin = min(kmin, k); kmax = max(kmax, k); }
+  });
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
   }
-  const unsigned long long before =
-      block_exclusive_scan<kThreads>((unsigned long long)gt | ((unsigned long long)eq << 32), wave_tot);
-  int gt_b = (int)(before & 0xffffffffull), eq_b = (int)(before >> 32);
-  for (int j = 0; j < nv; ++j) {
-    const uint32_t k = key_at(j);
-    if (k > T) {
-      out[gt_b + min(eq_b, need)] = first + j;
-      ++gt_b;
-    } else if (k == T) {
-      if (eq_b < need) out[gt_b + eq_b] = first + j;
-      ++eq_b;
+  if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
+  for (int i = t; i < kBuckets; i += kThreads) hist[i] = 0;
+  if (t == 0) s_ncand = 0;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) { kmin = min(kmin, wave_min[w]); kmax = max(kmax, wave_max[w]); }
+  float lo = 0.f, scale = 0.f;
+  if (kmin < kmax) {  // at least two distinct finite scores
+    lo = ordered_to_float(kmin);
+    const float range = ordered_to_float(kmax) - lo;
+    if (range > 0.f && range < 3.0e38f) scale = (float)(kBuckets - 1) / range;
+    if (!(scale < 3.0e38f)) scale = 0.f;  // a denormal range: leave everything in one bucket
+  }
+  auto bucket_of = [&](uint32_t k) { return linear_bucket(k, lo, scale, kBuckets); };
+  for_each_key([&](int, uint32_t k) { atomicAdd(&hist[bucket_of(k)], 1); });
+  __syncthreads();
+  {  // suffix scan over the buckets: thread t owns buckets kBuckets-1-2t and kBuckets-2-2t
+    const int c_hi = hist[kBuckets - 1 - 2 * t], c_lo = hist[kBuckets - 2 - 2 * t];
+    int above = (int)block_exclusive_scan<kThreads>((unsigned long long)(c_hi + c_lo), wave_tot);
+    if (above < kb && kb <= above + c_hi) { s_bucket = kBuckets - 1 - 2 * t; s_need = kb - above; }
+    above += c_hi;
+    if (above < kb && kb <= above + c_lo) { s_bucket = kBuckets - 2 - 2 * t; s_need = kb - above; }
+  }
+  __syncthreads();
+  const int bstar = s_bucket;
+  int need = s_need;  // how many of the boundary bucket's keys are selected
+  const int ncand = hist[bstar];
+
+  // ---- 2. exact threshold inside the boundary bucket: key T and how many keys equal to T to take
+  uint32_t T;
+  if (ncand <= kMaxRank) {
+    for_each_key([&](int page, uint32_t k) {
+      if (bucket_of(k) == bstar) {
+        const int slot = atomicAdd(&s_ncand, 1);
+        cand_key[slot] = k;
+        cand_idx[slot] = page;
+      }
+    });
+    __syncthreads();
+    if (t < ncand) {
+      const uint32_t mk = cand_key[t];
+      const int mi = cand_idx[t];
+      int rank = 0, greater = 0;
+      for (int j = 0; j < ncand; ++j) {
+        const uint32_t k = cand_key[j];
+        greater += k > mk;
+        rank += (k > mk) || (k == mk && cand_idx[j] < mi);
+      }
+      if (rank == need - 1) { s_prefix = mk; s_need = need - greater; }
+    }
+    __syncthreads();
+    T = s_prefix;
+    need = s_need;
+  } else {
+    T = radix_threshold<kThreads, 0>(
+        ipt, [&](int j) { return key_of(j * kThreads + t); },
+        [&](int j) { return j * kThreads + t < P && bucket_of(key_of(j * kThreads + t)) == bstar; }, need, hist,
+        &s_prefix, &s_need);
+  }
+
+  // ---- 3. compaction in page order. "gt": above the boundary; "eq": equal to the k-th key.
+  int gt_run = 0, eq_run = 0;  // such pages in the blocks already walked
+  constexpr int kAhead = 8;    // blocks whose keys are read together, ahead of the barriers that walk them
+  for (int base0 = 0, it = 0; base0 < P; base0 += kAhead * kThreads) {
+    uint32_t kk[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const int page = base0 + u * kThreads + t;
+      kk[u] = page < P ? key_of(page) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u, ++it) {
+      const int page = base0 + u * kThreads + t;
+      if (base0 + u * kThreads >= P) break;  // uniform
+      const int bk = page < P ? bucket_of(kk[u]) : -1;
+      const bool gt = bk > bstar || (bk == bstar && kk[u] > T), eq = bk == bstar && kk[u] == T;
+      const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      if (lane == 0) { wave_gt[it & 1][wave] = __popcll(bg); wave_eq[it & 1][wave] = __popcll(be); }
+      __syncthreads();  // the buffers alternate, so one barrier per block is enough
+      int gt_before = gt_run + __popcll(bg & below), eq_before = eq_run + __popcll(be & below);
+      int gt_block = 0, eq_block = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const int g = wave_gt[it & 1][w], e = wave_eq[it & 1][w];
+        gt_before += w < wave ? g : 0;
+        eq_before += w < wave ? e : 0;
+        gt_block += g;
+        eq_block += e;
+      }
+      if (gt) out[gt_before + min(eq_before, need)] = page;
+      else if (eq && eq_before < need) out[gt_before + eq_before] = page;
+      gt_run += gt_block;
+      eq_run += eq_block;
     }
   }
 }
@@ -345,6 +479,7 @@ hipError_t launch_select(const CacheView& c, const float* d_scores, int score_st
   if (P <= 8192) return launch_t<1024, 8>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 16384) return launch_t<1024, 16>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   if (P <= 32768) return launch_t<1024, 32>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
+  if (P <= 65536) return launch_t<1024, 64>(c, d_scores, score_stride, top_k, d_sel_pages, d_sel_count, stream);
   topk_select_long_kernel<1024><<<dim3(c.B * c.Hkv), dim3(1024), 0, stream>>>(c, d_scores, score_stride, top_k,
                                                                               d_sel_pages, d_sel_count);
   return hipGetLastError();

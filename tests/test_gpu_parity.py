@@ -234,19 +234,20 @@ SCORE_MAKERS = {
 
 
 @pytest.mark.parametrize("kind", sorted(SCORE_MAKERS))
-@pytest.mark.parametrize("P,top_k", [(200, 16), (3000, 64), (8192, 256), (20000, 1024)])
+@pytest.mark.parametrize("P,top_k", [(200, 16), (3000, 64), (8192, 256), (20000, 1024), (50000, 300)])
 def test_select_exact_on_crafted_scores(gpu_lib, kind, P, top_k):
     _crafted_select(P, top_k, SCORE_MAKERS[kind])
 
 
-@pytest.mark.parametrize("P", [255, 256, 257, 1024, 1025, 2048, 2049, 4096, 4097, 8193, 16384, 16385, 32768, 33000])
+@pytest.mark.parametrize("P", [255, 256, 257, 1024, 1025, 2048, 2049, 4096, 4097, 8193, 16384, 16385, 32768, 33000, 65537,
+                               100000])
 def test_select_row_length_boundaries(gpu_lib, P):
     _crafted_select(P, 37, SCORE_MAKERS["heavy_ties"])
     _crafted_select(P, P - 1, SCORE_MAKERS["normal"])
 
 
 @pytest.mark.parametrize("kind", ["normal", "heavy_ties", "descending", "nan_and_inf", "all_equal"])
-@pytest.mark.parametrize("P,top_k", [(200, 16), (8192, 256), (40000, 64)])
+@pytest.mark.parametrize("P,top_k", [(200, 16), (8192, 256), (40000, 64), (70001, 1000)])
 @pytest.mark.parametrize("n", [1, 3, "k", "k+5"])
 def test_forced_recent_pages_on_crafted_scores(gpu_lib, kind, P, top_k, n):
     """force_recent_pages: the last pages are selected whatever they score (descending scores rank them last, NaN
