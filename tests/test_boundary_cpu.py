@@ -139,3 +139,20 @@ def test_binding_raises_with_detail(lib):
     with pytest.raises(binding.UniqueError) as e:
         lib.workspace_bytes(good_desc(head_dim=80), 4)
     assert e.value.code == binding.ERR_UNSUPPORTED and "head_dim=80" in str(e.value)
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(lib, tmp_path):
+    """include/unique.h compiles as strict C99 and a C program linked against the library gets version, status
+    strings and host-side validation errors without a GPU (tests/c_abi/abi_check.c)."""
+    import subprocess
+    from paper_2605_27740_amd import build as B
+    exe = str(tmp_path / "abi_check")
+    libdir = os.path.dirname(B.LIB_PATH)
+    libname = os.path.basename(B.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi", "abi_check.c"), "-o", exe, "-L", libdir, f"-l:{libname}",
+           f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert "unique-gfx950" in r.stdout
