@@ -51,3 +51,21 @@ def build_library(force: bool = False, extra_flags: list[str] | None = None, job
 
 if __name__ == "__main__":
     print(build_library(force=True))
+
+
+C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "gpu_client.c")
+C_CLIENT_BIN = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "gpu_client.bin")
+
+
+def build_c_client(force: bool = False) -> str:
+    """Compile the plain-C client of the ABI (tests/c_abi/gpu_client.c) with gcc against the built library and the
+    HIP runtime's C API; the GPU tests run the resulting program."""
+    if force or not os.path.exists(C_CLIENT_BIN) or os.path.getmtime(C_CLIENT_BIN) < max(
+            os.path.getmtime(C_CLIENT_SRC), os.path.getmtime(LIB_PATH)):
+        rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+        cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include",
+               "-I" + os.path.join(os.path.dirname(HERE), "include"), C_CLIENT_SRC, "-o", C_CLIENT_BIN,
+               "-L" + os.path.dirname(LIB_PATH), "-l:" + os.path.basename(LIB_PATH), f"-L{rocm}/lib", "-lamdhip64", "-lm",
+               "-Wl,-rpath,$ORIGIN/../../paper_2605_27740_amd", f"-Wl,-rpath,{rocm}/lib"]
+        subprocess.run(cmd, check=True)
+    return C_CLIENT_BIN

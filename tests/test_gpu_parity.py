@@ -671,3 +671,14 @@ def test_config5_full_size_sampled(gpu_lib, top_k):
     wl = W.config5(device=DEV, top_k=top_k)
     _, rep = Hn.full_check(wl, rows=[(0, 1), (3, 2)], dense_heads=[(3, 9)])
     say(rep)
+
+
+def test_a_plain_c_client_runs_the_whole_path(gpu_lib):
+    """tests/c_abi/gpu_client.c: statistics, one decode step and the dense decode through the C ABI from a C program
+    that uses only the HIP runtime's C API, checked inside that program against Eq. 1-6 evaluated in double."""
+    import subprocess
+    from paper_2605_27740_amd import build as B
+    exe = B.build_c_client()        # built beforehand by __graft_entry__.build(); compiled here only if missing
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    say(r.stdout.strip())
+    assert r.returncode == 0, (r.returncode, r.stdout[-2000:], r.stderr[-2000:])
