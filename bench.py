@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--top-k", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None,
+                    help="with --workload c3: another batch size (the workload name in the JSON line says so)")
+    ap.add_argument("--context", type=int, default=None, help="with --workload c3: another context length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--stats-dtype", default="fp32", choices=["fp32", "bf16"],
@@ -97,7 +100,15 @@ def main():
 
     t0 = time.time()
     kw = {} if args.top_k is None else {"top_k": args.top_k}
+    if args.batch is not None or args.context is not None:
+        assert args.workload == "c3", "--batch / --context vary the c3 recipe only"
+        if args.batch is not None:
+            kw["batch"] = args.batch
+        if args.context is not None:
+            kw["context"] = args.context
     wl = {"c2": W.config2, "c3": W.config3, "c4": W.config4, "c5": W.config5}[args.workload](device=dev, **kw)
+    if args.batch is not None or args.context is not None:
+        wl.name = f"c3_recipe_b{wl.B}_ctx{max(wl.seq_lens.tolist())}"   # not the BASELINE configuration
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     sess = DecodeSession(wl, want_scores=False, stats_dtype=stats_dtype)
