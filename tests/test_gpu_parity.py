@@ -403,6 +403,37 @@ def test_random_shape_sweep(gpu_lib, seed):
     assert torch.equal(keep[1].view(torch.uint8), sess.out.view(torch.uint8))
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_medium_shape_sweep(gpu_lib, seed):
+    """Seeded random draws at sizes where the launch plans change (contexts up to 150K tokens, every supported shape,
+    k up to 600, both statistics formats, optional always-keep pages): sampled rows against the oracle, and the
+    one-call step bit-identical to the separate calls."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = torch.bfloat16 if rng.random() < 0.8 else torch.float32
+    D = int(rng.choice([64, 128]))
+    S = int(rng.choice([8, 16, 32]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    B = int(rng.integers(1, 6))
+    top = 150000 if Hkv * D <= 1024 else 40000
+    lens = [int(x) for x in np.exp(rng.uniform(np.log(1), np.log(top), size=B)).round().clip(1, top)]
+    k = int(np.exp(rng.uniform(0, np.log(600))))
+    sd = [torch.float32, torch.bfloat16][int(rng.integers(2))]
+    forced = int(rng.choice([0, 0, 3]))
+    say(f"seed {seed}: {dtype} D={D} S={S} G={G} Hkv={Hkv} lens={lens} k={k} stats={sd} forced={forced}")
+    wl = W.build("med", 30 + seed % 7, dtype=dtype, B=B, H=G * Hkv, Hkv=Hkv, D=D, S=S, seq_lens=lens, top_k=k,
+                 key_mode=["iid", "shift", "ar1"][int(rng.integers(3))], plant_mode="one_percent",
+                 permute=bool(rng.integers(2)), spare_tokens=S, device=DEV, poison=True)
+    sess = DecodeSession(wl, stats_dtype=sd, force_recent_pages=forced)
+    rows = [(int(rng.integers(B)), int(rng.integers(Hkv))) for _ in range(3)] + [(int(np.argmax(lens)), Hkv - 1)]
+    sess, rep = Hn.full_check(wl, sess=sess, rows=sorted(set(rows)), stats_dtype=sd)
+    say(rep)
+    keep = (sess.sel_pages.clone(), sess.out.clone())
+    sess.decode_step(refresh_tail=True)
+    torch.cuda.synchronize()
+    assert torch.equal(keep[0], sess.sel_pages) and torch.equal(keep[1].view(torch.uint8), sess.out.view(torch.uint8))
+
+
 @pytest.mark.parametrize("Hkv,width", [(8, 4096), (8, 8192), (16, 8192), (32, 8192)])
 def test_wide_page_tables_take_the_larger_score_tiles(gpu_lib, Hkv, width):
     """The score kernel sizes its grid from the page-table width (no length hint given) and moves from 32-page
