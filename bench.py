@@ -108,7 +108,7 @@ def main():
             kw["context"] = args.context
     wl = {"c2": W.config2, "c3": W.config3, "c4": W.config4, "c5": W.config5}[args.workload](device=dev, **kw)
     if args.batch is not None or args.context is not None:
-        wl.name = f"c3_recipe_b{wl.B}_ctx{max(wl.seq_lens.tolist())}"   # not the BASELINE configuration
+        wl.name = f"c3_recipe_b{wl.B}_ctx{max(wl.seq_lens.tolist())}"   # a variation, not the 128K benchmark configuration
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     sess = DecodeSession(wl, want_scores=False, stats_dtype=stats_dtype)
