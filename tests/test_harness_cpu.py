@@ -37,6 +37,23 @@ def test_selection_rule_accepts_exact_and_band_swaps_only():
     assert Hn.check_selection_row(np.array([0, 1, 2, 3, 4, -1], np.int32), 5, s2, 6)
 
 
+def test_selection_rule_with_always_kept_pages():
+    s = np.array([5.0, 1.0, 4.0, 3.0, 0.2, 0.1, 0.3])          # the last two pages score lowest
+    # k = 4, the last 2 pages forced: {5, 6} plus the best two of the rest {0, 2}
+    assert Hn.check_selection_row(np.array([0, 2, 5, 6], np.int32), 4, s, 4, force_recent=2)
+    assert Hn.check_selection_row(np.array([0, 2, 5, 6, -1], np.int32), 4, s, 4, force_recent=2)
+    with pytest.raises(AssertionError):                 # plain top-4 ignores the forced pages
+        Hn.check_selection_row(np.array([0, 2, 3, 6], np.int32), 4, s, 4, force_recent=2)
+    with pytest.raises(AssertionError):                 # forced pages there, but the rest is not the best of the others
+        Hn.check_selection_row(np.array([0, 3, 5, 6], np.int32), 4, s, 4, force_recent=2)
+    with pytest.raises(AssertionError):                 # the same set is wrong when nothing is forced
+        Hn.check_selection_row(np.array([0, 2, 5, 6], np.int32), 4, s, 4)
+    # n >= k: exactly the last k pages
+    assert Hn.check_selection_row(np.array([4, 5, 6], np.int32), 3, s, 3, force_recent=5)
+    with pytest.raises(AssertionError):
+        Hn.check_selection_row(np.array([0, 5, 6], np.int32), 3, s, 3, force_recent=5)
+
+
 def test_attention_rule_flags_a_wrong_output():
     c, q = make_case(21, lens=(13, 7))
     pages = [0, 2]
