@@ -80,6 +80,33 @@ constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
 constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
 
+// Minimum / maximum of an unsigned value over the 64 lanes of a wave (every lane gets the result): four DPP
+// exchanges inside the rows of 16 lanes, then two cross-row shuffles.
+template <bool kMax>
+__device__ __forceinline__ uint32_t wave_allreduce_minmax(uint32_t x) {
+  auto op = [](uint32_t a, uint32_t b) { return kMax ? (a > b ? a : b) : (a < b ? a : b); };
+  x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kDppXor1, 0xf, 0xf, true));
+  x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kDppXor2, 0xf, 0xf, true));
+  x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kDppHalfMirror, 0xf, 0xf, true));
+  x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kDppMirror, 0xf, 0xf, true));
+  x = op(x, (uint32_t)__shfl_xor((int)x, 16, kWave));
+  x = op(x, (uint32_t)__shfl_xor((int)x, 32, kWave));
+  return x;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave: four row shifts inside each row of 16 lanes (a lane whose
+// source lies outside its row adds 0), then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to
+// rows 2 and 3. No LDS traffic.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 struct OpSum { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
 struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
 

@@ -24,16 +24,15 @@ constexpr int kMaxRankCandidates = 512;  // above this the boundary bucket is re
 constexpr uint32_t kKeyForced = 0xffffffffu;  // key of a page that is selected whatever its score
 constexpr uint32_t kKeyNegInf = 0x007fffffu, kKeyPosInf = 0xff800000u;  // keys of -inf and +inf
 
+// Exclusive prefix sums of two counters at once over the threads of a workgroup (thread order). The pair
+// travels packed in 64 bits; wave_tot: kThreads / 64 slots of LDS. All threads must call it.
 template <int kThreads>
 __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long v,
                                                                   unsigned long long* wave_tot /*[kThreads/64]*/) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  unsigned long long inc = v;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const unsigned long long o = __shfl_up(inc, off, kWave);
-    if (lane >= off) inc += o;
-  }
+  const int lo = (int)(v & 0xffffffffull), hi = (int)(v >> 32);
+  const int inc_lo = wave_inclusive_scan(lo), inc_hi = wave_inclusive_scan(hi);
+  const unsigned long long inc = (unsigned long long)(uint32_t)inc_lo | ((unsigned long long)(uint32_t)inc_hi << 32);
   if (lane == kWave - 1) wave_tot[wave] = inc;
   __syncthreads();
   unsigned long long base = 0;
@@ -187,11 +186,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(CacheView c, cons
   for (int j = 0; j < kItems; ++j) {
     if (j < nv && key[j] > kKeyNegInf && key[j] < kKeyPosInf) { kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
-  }
+  kmin = wave_allreduce_minmax<false>(kmin);
+  kmax = wave_allreduce_minmax<true>(kmax);
   if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
   for (int i = t; i < kBuckets; i += kThreads) hist[i] = 0;
   if (t == 0) s_ncand = 0;
@@ -357,11 +353,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_long_kernel(CacheView c,
   for_each_key([&](int, uint32_t k) {
     if (k > kKeyNegInf && k < kKeyPosInf) { kmin = min(kmin, k); kmax = max(kmax, k); }
   });
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, kWave));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, kWave));
-  }
+  kmin = wave_allreduce_minmax<false>(kmin);
+  kmax = wave_allreduce_minmax<true>(kmax);
   if (lane == 0) { wave_min[wave] = kmin; wave_max[wave] = kmax; }
   for (int i = t; i < kBuckets; i += kThreads) hist[i] = 0;
   if (t == 0) s_ncand = 0;
