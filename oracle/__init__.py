@@ -49,8 +49,9 @@ def _load():
         _lib = C.CDLL(_LIB)
         for name in ("oracle_page_stats", "oracle_page_scores", "oracle_topk", "oracle_attention",
                      "oracle_update_stats", "oracle_sparse_decode_step", "oracle_dense_decode",
-                     "oracle_num_threads"):
+                     "oracle_attention_rows", "oracle_num_threads"):
             getattr(_lib, name).restype = C.c_int
+        _lib.oracle_round_bf16.restype = None
     return _lib
 
 
@@ -136,7 +137,7 @@ def topk(scores: np.ndarray, k: int):
 
 
 def topk_forced(scores: np.ndarray, k: int, force_recent: int):
-    """Selection with the always-keep option of the C ABI (a serving option, not part of the paper: Section 4.2
+    """Selection with the always-keep option of the C ABI (a serving option, not part of the paper: Section 4.3
     states that the method needs no local window, so force_recent = 0 is the paper's behaviour). The last
     n = min(force_recent, k, P) logical pages are selected whatever their scores; the other min(k, P) - n places
     go to the best of the remaining pages under the (score desc, index asc) ranking.
@@ -219,3 +220,35 @@ def dense_decode(c: OracleCache, q: np.ndarray, sm_scale: float = 0.0):
     if rc != 0:
         raise ValueError(f"oracle_dense_decode failed with {rc}")
     return out, lse
+
+
+def attention_rows(c: OracleCache, q: np.ndarray, sel: np.ndarray, sel_count: np.ndarray, sm_scale: float = 0.0):
+    """Eq. 5 for every (b, h) over the given page lists: sel int32 [B, Hkv, stride] (the first sel_count[b, hkv]
+    entries of a row are used) -> (out [B, H, D], lse [B, H]); an empty row gives zeros and lse = -inf."""
+    c._check_q(q)
+    sel = np.ascontiguousarray(sel, np.int32)
+    sel_count = np.ascontiguousarray(sel_count, np.int32)
+    assert sel.shape[:2] == (c.B, c.Hkv) and sel_count.shape == (c.B, c.Hkv)
+    assert int(sel_count.max(initial=0)) <= sel.shape[2]
+    out = np.zeros((c.B, c.H, c.D), np.float64)
+    lse = np.zeros((c.B, c.H), np.float64)
+    rc = _load().oracle_attention_rows(C.byref(c._c), _ptr(q), _ptr(sel), _ptr(sel_count), int(sel.shape[2]),
+                                       C.c_double(sm_scale), _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError(f"oracle_attention_rows failed with {rc}")
+    return out, lse
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """bf16 storage of the page means (the paper's storage format, Appendix A): each float64 rounded once to the
+    nearest bfloat16, ties to even -> uint16 bit patterns of the same shape."""
+    x = np.ascontiguousarray(x, np.float64)
+    bits = np.zeros(x.shape, np.uint16)
+    _load().oracle_round_bf16(_ptr(x), C.c_int64(x.size), _ptr(bits))
+    return bits
+
+
+def bf16_to_double(bits: np.ndarray) -> np.ndarray:
+    """The float64 value of bf16 bit patterns (exact)."""
+    bits = np.ascontiguousarray(bits, np.uint16)
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

@@ -21,6 +21,9 @@
  *   - no page is kept unconditionally: exactly min(k, P) pages, all chosen by score;
  *   - N counts the token being decoded.
  *
+ *   - bf16 storage of the page means (the storage format of the paper's kernels, Appendix A "in bf16"):
+ *     the float64 mean of Eq. 1 rounded once, to nearest with ties to even, by oracle_round_bf16.
+ *
  * Every function has an independent pin in tests/test_oracle_pins.py
  * (brute force in pure Python, closed forms, invariants, numpy special cases).
  *
@@ -209,6 +212,33 @@ int oracle_attention(const oracle_cache* c, const void* q, int b, int h,
   return 0;
 }
 
+/* bfloat16 (1 sign, 8 exponent, 7 fraction bits) nearest to each double, ties to the even fraction, as bit
+ * patterns. The rounding is done on the double itself (never through float first, which would round twice):
+ * a finite non-zero x lies in [2^e, 2^(e+1)); bf16 numbers there are multiples of ulp = 2^(e-7) (2^-133 in the
+ * subnormal range e < -126); x / ulp is exact in double and rint() rounds it half-to-even. A result of 2^128 or
+ * more is infinity. NaN gives a quiet NaN. */
+void oracle_round_bf16(const double* x, int64_t n, uint16_t* bits) {
+  for (int64_t i = 0; i < n; ++i) {
+    const double v = x[i];
+    const uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    if (isnan(v)) { bits[i] = 0x7fc0u; continue; }
+    const double a = fabs(v);
+    if (isinf(a)) { bits[i] = (uint16_t)(sign | 0x7f80u); continue; }
+    if (a == 0.0) { bits[i] = sign; continue; }
+    int ex;
+    (void)frexp(a, &ex);           /* a = m * 2^ex with m in [0.5, 1) */
+    int e = ex - 1;                /* a in [2^e, 2^(e+1)) */
+    if (e < -126) e = -126;        /* subnormals share the spacing of the smallest normal binade */
+    const double ulp = ldexp(1.0, e - 7);
+    const double r = rint(a / ulp) * ulp;   /* default rounding mode: nearest, ties to even */
+    if (r >= ldexp(1.0, 128)) { bits[i] = (uint16_t)(sign | 0x7f80u); continue; }
+    const float f = (float)r;      /* exact: r has at most 8 significant bits and is within float range */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    bits[i] = (uint16_t)(sign | (uint16_t)(u >> 16));
+  }
+}
+
 /* ---- whole-batch drivers (the same functions, looped over rows with OpenMP) ---- */
 
 /* Stats of every logical page of every (b, hkv) that overlaps tokens
@@ -294,6 +324,33 @@ int oracle_dense_decode(const oracle_cache* c, const void* q, double sm_scale, d
     for (int p = 0; p < P; ++p) all[p] = p;
     int rc = oracle_attention(c, q, b, h, all, P, sm_scale, out + (int64_t)r * c->D, lse + r);
     free(all);
+    if (rc != 0) {
+#pragma omp atomic write
+      err = rc;
+    }
+  }
+  return err;
+}
+
+/* Eq. 5 for every (b, h) over a GIVEN page list per (b, kv head): sel [B][Hkv][sel_stride] logical pages (the first
+ * sel_count[b][hkv] entries of a row are used). A row with no entries gives a zero output and lse = -inf.
+ * out: [B][H][D]; lse: [B][H]. */
+int oracle_attention_rows(const oracle_cache* c, const void* q, const int32_t* sel, const int32_t* sel_count,
+                          int sel_stride, double sm_scale, double* out, double* lse) {
+  const int rows = c->B * c->H, G = c->H / c->Hkv;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int r = 0; r < rows; ++r) {
+    const int b = r / c->H, h = r % c->H, hkv = h / G;
+    const int64_t lrow = (int64_t)b * c->Hkv + hkv;
+    const int n = sel_count[lrow];
+    int rc = 0;
+    if (n <= 0) {
+      for (int d = 0; d < c->D; ++d) out[(int64_t)r * c->D + d] = 0.0;
+      lse[r] = -INFINITY;
+    } else {
+      rc = oracle_attention(c, q, b, h, sel + lrow * sel_stride, n, sm_scale, out + (int64_t)r * c->D, lse + r);
+    }
     if (rc != 0) {
 #pragma omp atomic write
       err = rc;

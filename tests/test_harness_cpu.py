@@ -73,3 +73,40 @@ def test_attention_rule_flags_a_wrong_output():
     bad_lse[0, 1] += 1e-2
     with pytest.raises(AssertionError):
         Hn.check_attention_head(out, bad_lse, c, q, 0, 1, pages, torch.float32)
+
+
+def test_bf16_mean_rule_accepts_the_oracle_rounding_and_justified_neighbours_only():
+    """Stored bf16 means have to be the oracle's float64 means rounded once; a neighbouring bf16 value passes only
+    where the float64 mean sits within the fp32 accumulation bound of the rounding boundary."""
+    rng = np.random.default_rng(5)
+    mean = rng.normal(size=(6, 16)) * 0.5
+    n_keys, abs_mean = 16.0, 0.8
+    akm = lambda idx: (np.full(idx[0].shape, abs_mean), np.full(idx[0].shape, n_keys))
+    good = oracle.round_bf16(mean)
+    used, (n, worst) = Hn.check_bf16_means(good.copy(), mean, akm)
+    assert n == 0 and worst == 0.0 and np.array_equal(used, oracle.bf16_to_double(good))
+    # a neighbour where the mean is far from the boundary: rejected
+    bad = good.copy()
+    bad[2, 3] += 1
+    with pytest.raises(AssertionError):
+        Hn.check_bf16_means(bad, mean, akm)
+    # two values away: rejected whatever the mean
+    bad2 = good.copy()
+    bad2[1, 1] += 2
+    with pytest.raises(AssertionError):
+        Hn.check_bf16_means(bad2, mean, akm)
+    # a mean placed 1e-7 of its size beside a rounding boundary: both neighbours pass, and the one the kernel stored is
+    # what the later stages are checked with
+    lo, hi = oracle.bf16_to_double(np.array([0x3F00, 0x3F01], np.uint16))      # 0.5 and the next bf16 value
+    mean2 = mean.copy()
+    mean2[4, 7] = 0.5 * (lo + hi) + 2e-8
+    want = oracle.round_bf16(mean2)
+    assert want[4, 7] == 0x3F01
+    other = want.copy()
+    other[4, 7] = 0x3F00
+    used, (n, worst) = Hn.check_bf16_means(other, mean2, akm)
+    assert n == 1 and 0 < worst <= 1.0 and used[4, 7] == lo
+    # the same neighbour with the mean 1e-5 away from the boundary: outside the bound, rejected
+    mean2[4, 7] = 0.5 * (lo + hi) + 1e-5
+    with pytest.raises(AssertionError):
+        Hn.check_bf16_means(other, mean2, akm)

@@ -479,7 +479,7 @@ def test_planted_keys_need_the_std_offset():
 
 
 def test_topk_forced_recent_pages_invariants():
-    """The always-keep option (C ABI; not from the paper, whose method needs no local window -- Section 4.2):
+    """The always-keep option (C ABI; not from the paper, whose method needs no local window -- Section 4.3):
     the set has min(k, P) pages, contains the last min(n, k, P), and among the other pages every selected one
     outranks every unselected one under (score desc, index asc); n = 0 is the plain top-k."""
     rng = np.random.default_rng(5)
@@ -500,3 +500,106 @@ def test_topk_forced_recent_pages_invariants():
         for a in chosen:
             for b in others:
                 assert (s[a], -a) > (s[b], -b), (trial, a, b)
+
+
+# ------------------------------------------------------------------ bf16 storage of the means (oracle_round_bf16)
+
+def _all_bf16_values():
+    """Every finite bf16 value >= 0 in ascending order with its bit pattern (exhaustive table, 32640 entries)."""
+    bits = np.arange(0x0000, 0x7F80, dtype=np.uint16)
+    return bf16_bits_to_f64(bits), bits
+
+
+def _nearest_bf16_brute(x: float) -> int:
+    """Nearest bf16 bit pattern of a finite double by exhaustive comparison in exact rational arithmetic;
+    ties go to the even fraction (even bit pattern); beyond the largest finite value the midpoint to 2^128 decides."""
+    from fractions import Fraction
+    vals, bits = _all_bf16_values()
+    sign = 0x8000 if math.copysign(1.0, x) < 0 else 0
+    a = Fraction(abs(x))
+    i = int(np.searchsorted(vals, float(abs(x)), side="right")) - 1      # vals[i] <= |x|
+    lo = Fraction(float(vals[i]))
+    hi = Fraction(float(vals[i + 1])) if i + 1 < len(vals) else Fraction(2) ** 128
+    hi_bits = int(bits[i + 1]) if i + 1 < len(vals) else 0x7F80
+    if a - lo < hi - a:
+        return sign | int(bits[i])
+    if a - lo > hi - a:
+        return sign | hi_bits
+    return sign | (int(bits[i]) if int(bits[i]) % 2 == 0 else hi_bits)
+
+
+def test_round_bf16_against_exhaustive_search():
+    rng = np.random.default_rng(31)
+    x = np.concatenate([
+        rng.normal(size=600), rng.normal(size=300) * 1e-3, rng.normal(size=200) * 1e30, rng.normal(size=200) * 1e-39,
+        np.ldexp(rng.uniform(1, 2, size=300), rng.integers(-140, 128, size=300)) * rng.choice([-1, 1], size=300),
+        [0.0, -0.0, 1.0, -1.0, 3.3895313892515355e38, 3.3961775292304601e38, 3.4e38, -3.4e38, 1e-45, 4.6e-41, 9.2e-41],
+    ])
+    got = oracle.round_bf16(x)
+    want = np.array([_nearest_bf16_brute(float(v)) for v in x], np.uint16)
+    assert np.array_equal(got, want), np.nonzero(got != want)[0][:10]
+
+
+def test_round_bf16_rounds_once_and_ties_to_even():
+    """Values that separate one rounding of the double from a rounding through float first, and exact ties."""
+    cases = {
+        1.0 + 2.0 ** -8 + 2.0 ** -40: 0x3F81,   # just above a tie: up (through float it becomes the tie and goes down)
+        1.0 + 2.0 ** -8 - 2.0 ** -40: 0x3F80,
+        1.0 + 2.0 ** -8: 0x3F80,                # tie -> even fraction 0000000
+        1.0 + 3 * 2.0 ** -8: 0x3F82,            # tie -> even fraction 0000010
+        -(1.0 + 3 * 2.0 ** -8): 0xBF82,
+        0.5 - 2.0 ** -10: 0x3F00,               # tie just below a power of two (spacing halves there) -> 0.5
+        2.0 ** -133: 0x0001, 2.0 ** -134: 0x0000, 3 * 2.0 ** -134: 0x0002,   # subnormals, ties to even
+        float("inf"): 0x7F80, float("-inf"): 0xFF80,
+    }
+    x = np.array(list(cases), np.float64)
+    assert oracle.round_bf16(x).tolist() == list(cases.values())
+    assert oracle.round_bf16(np.array([float("nan")]))[0] & 0x7FC0 == 0x7FC0
+    assert math.copysign(1.0, oracle.bf16_to_double(oracle.round_bf16(np.array([-0.0])))[0]) == -1.0
+
+
+def test_round_bf16_equals_the_bit_trick_on_float32_inputs():
+    """A double that is exactly a float32 rounds like the usual add-0x7fff-plus-lsb integer trick on its bits
+    (written independently above), and rounding is idempotent on bf16 values."""
+    rng = np.random.default_rng(32)
+    x = (rng.normal(size=20000) * np.exp(rng.uniform(-60, 60, size=20000))).astype(np.float32)
+    x = x[np.isfinite(x)]
+    assert np.array_equal(oracle.round_bf16(x.astype(np.float64)), f32_to_bf16_bits(x))
+    vals, bits = _all_bf16_values()
+    assert np.array_equal(oracle.round_bf16(vals), bits) and np.array_equal(oracle.bf16_to_double(bits), vals)
+
+
+# ------------------------------------------------------------------ Eq. 5 over given page lists, whole batch
+
+def test_attention_rows_equals_the_definition_head_by_head():
+    c, q = make_case(41, B=3, H=4, Hkv=2, D=8, S=4, lens=(13, 7, 22), spare_pages=0)
+    rng = np.random.default_rng(41)
+    stride = 5
+    sel = np.full((c.B, c.Hkv, stride), -1, np.int32)
+    cnt = np.zeros((c.B, c.Hkv), np.int32)
+    for b in range(c.B):
+        for h in range(c.Hkv):
+            n = int(rng.integers(1, min(stride, c.num_pages(b)) + 1))
+            sel[b, h, :n] = rng.permutation(c.num_pages(b))[:n]       # any order, distinct
+            cnt[b, h] = n
+    cnt[1, 0] = 0                                                      # an empty list
+    out, lse = oracle.attention_rows(c, q, sel, cnt, 0.3)
+    assert (out[1, :c.G] == 0).all() and np.isneginf(lse[1, :c.G]).all()
+    kf, vf = as_f64(c.k_cache).tolist(), as_f64(c.v_cache).tolist()
+    for b in range(c.B):
+        for h in range(c.H):
+            hkv = h // c.G
+            if cnt[b, hkv] == 0:
+                continue
+            pages = sel[b, hkv, :cnt[b, hkv]].tolist()
+            toks = brute.tokens_of(int(c.seq_lens[b]), c.S, pages)
+            o_b, l_b = brute.softmax_attention([float(x) for x in as_f64(q[b, h])],
+                                               brute.key_rows(kf, c.page_table[b].tolist(), c.S, hkv, toks),
+                                               brute.key_rows(vf, c.page_table[b].tolist(), c.S, hkv, toks), 0.3)
+            assert np.allclose(out[b, h], o_b, rtol=1e-12, atol=1e-13) and abs(lse[b, h] - l_b) < 1e-12
+    # on the oracle's own selection it reproduces the whole-step driver
+    mean_all, std_all = oracle.new_stat_cache(c)
+    oracle.update_stats(c, mean_all, std_all)
+    r = oracle.sparse_decode_step(c, q, mean_all, std_all, 0.5, 3)
+    o2, l2 = oracle.attention_rows(c, q, r["sel"], r["sel_count"])
+    assert np.array_equal(o2, r["out"]) and np.array_equal(l2, r["lse"])
