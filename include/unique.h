@@ -91,7 +91,7 @@ typedef struct unique_cache_desc {
   int32_t force_recent_pages; /* >= 0. n > 0: the last min(n, k, P) logical pages of every sequence are always part of
                                 the selection (they take the places of the lowest-ranked of the k); the other
                                 places go to the best-scoring remaining pages. 0 = the paper's method, which
-                                needs no local window (Section 4.2). A serving safety option, not from the paper. */
+                                needs no local window (Section 4.3, long-form speech recognition). A serving safety option, not from the paper. */
   int64_t kv_page_stride;    /* elements between consecutive physical pages of k_cache (the same for v_cache);
                                 0 = H_kv*S*D (pages packed) */
   int64_t kv_head_stride;    /* elements between consecutive KV heads inside a page; 0 = S*D (heads packed).
