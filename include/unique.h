@@ -177,6 +177,22 @@ int unique_decode_step(const unique_cache_desc* desc, const void* d_q, int32_t t
                        int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out,
                        float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* unique_decode_step for callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same results, bit for
+ * bit, but the score rows and split-K partials live in a scratch array of UNIQUE_STATIC_SCRATCH_BYTES that is part
+ * of the library's device image (each GPU the library runs on holds its own copy until the process ends). The call
+ * allocates and frees nothing and calls no allocating routine; inputs and outputs are still the caller's.
+ *   - A step that needs more scratch than that (unique_workspace_bytes says how much a descriptor and top_k need)
+ *     returns UNIQUE_ERR_WORKSPACE and launches nothing; use unique_decode_step then.
+ *   - The device that owns `stream` must be the current device. The first call on a device looks up the array's
+ *     address there (no allocation); make that first call outside graph capture.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams or threads)
+ *     race on it. Nothing in it has to start at zero and nothing is carried from one call to the next. */
+#define UNIQUE_STATIC_SCRATCH_BYTES (8u << 20)
+int unique_decode_step_static(const unique_cache_desc* desc, const void* d_q, int32_t top_k, float lambda,
+                              float sm_scale, int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count,
+                              void* d_out, float* d_lse_out, void* stream);
+
 /* Dense paged decode attention, Eq. 4: the same kernels with every page of each sequence attended. */
 int unique_dense_paged_decode(const unique_cache_desc* desc, const void* d_q, float sm_scale, void* d_out,
                               float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream);

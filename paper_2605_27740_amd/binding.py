@@ -18,7 +18,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 DTYPE_CODE = {torch.float32: 0, torch.bfloat16: 1}
 
 EXPORTS = ("unique_workspace_bytes", "unique_page_stats_record_bytes", "unique_update_page_stats", "unique_score_select_topk",
-           "unique_page_scores", "unique_select_topk", "unique_decode_step", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
+           "unique_page_scores", "unique_select_topk", "unique_decode_step", "unique_decode_step_static", "unique_sparse_paged_decode", "unique_dense_paged_decode", "unique_status_string",
            "unique_last_error", "unique_version")
 
 
@@ -73,6 +73,9 @@ class Library:
         self.c.unique_decode_step.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_float, C.c_float,
                                               C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_size_t, C.c_void_p]
+        self.c.unique_decode_step_static.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_int32, C.c_float, C.c_float,
+                                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p]
         self.c.unique_dense_paged_decode.argtypes = [C.POINTER(CacheDesc), C.c_void_p, C.c_float, C.c_void_p,
                                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 
@@ -128,6 +131,11 @@ class Library:
                                              _p(sel_pages), _p(sel_count), _p(out), _p(lse_out), _p(workspace),
                                              workspace.numel() * workspace.element_size(), _stream()))
 
+    def decode_step_static(self, desc: CacheDesc, q, top_k: int, lam: float, sm_scale: float, refresh_tail: bool,
+                           sel_pages, sel_count, out, lse_out):
+        self.check(self.c.unique_decode_step_static(C.byref(desc), _p(q), top_k, lam, sm_scale, int(refresh_tail),
+                                                    _p(sel_pages), _p(sel_count), _p(out), _p(lse_out), _stream()))
+
     def dense_paged_decode(self, desc: CacheDesc, q, sm_scale: float, out, lse_out, workspace):
         self.check(self.c.unique_dense_paged_decode(C.byref(desc), _p(q), sm_scale, _p(out), _p(lse_out),
                                                     _p(workspace), workspace.numel() * workspace.element_size(),
@@ -148,6 +156,7 @@ def load() -> Library:
     return _lib
 
 
+STATIC_SCRATCH_BYTES = 8 << 20  # UNIQUE_STATIC_SCRATCH_BYTES
 STD_BLOCK_BYTES = 128  # bytes after the means in a page_stats record (fp32 stds + pad)
 
 

@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "kernels.hpp"
 
@@ -114,11 +115,72 @@ size_t decode_bytes(const unique::CacheView& v, int max_list_len) {
 }
 
 
+// Scratch of unique_decode_step_static: score rows, then split-K partials, of one call at a time per GPU. In host
+// code the array's name only stands for the symbol; its device address is looked up once per device below and
+// that pointer is what kernels and everything else get.
+static __device__ __align__(256) unsigned char scratch[UNIQUE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device: each GPU holds its own copy of the array at its own address
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(UNIQUE_ERR_UNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || ((uintptr_t)p % kAlign)) return fail(UNIQUE_ERR_HIP, "static scratch has no usable device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return UNIQUE_OK;
+}
+
 int check_workspace(const void* ws, size_t have, size_t need) {
   if (!ws) return fail(UNIQUE_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
   if ((uintptr_t)ws % kAlign) return fail(UNIQUE_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kAlign);
   if (have < need) return fail(UNIQUE_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", have, need);
   return UNIQUE_OK;
+}
+
+// Host-side validation shared by the two decode-step entry points; *region = bytes of scratch the step needs.
+int decode_step_check(const unique_cache_desc* desc, const void* d_q, int32_t top_k, float lambda, float sm_scale,
+                      const int32_t* d_sel_pages, const int32_t* d_sel_count, const void* d_out, unique::CacheView* v,
+                      size_t* region) {
+  const int rc = make_view(desc, v, true, true);
+  if (rc != UNIQUE_OK) return rc;
+  if (!d_q || !d_sel_pages || !d_sel_count || !d_out)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_q, d_sel_pages, d_sel_count and d_out must be non-NULL");
+  if (((uintptr_t)d_q | (uintptr_t)d_out) & 15u)
+    return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_out must be 16-byte aligned");
+  if (top_k < 1) return fail(UNIQUE_ERR_INVALID_ARG, "top_k must be >= 1 (got %d)", top_k);
+  if (!(lambda >= 0.f)) return fail(UNIQUE_ERR_INVALID_ARG, "lambda must be >= 0");
+  if (!(sm_scale == sm_scale)) return fail(UNIQUE_ERR_INVALID_ARG, "sm_scale is NaN");
+  const int list_len = top_k < v->max_pages_hint ? top_k : v->max_pages_hint;
+  *region = score_bytes(*v);
+  if (decode_bytes(*v, list_len) > *region) *region = decode_bytes(*v, list_len);
+  return UNIQUE_OK;
+}
+
+// Score -> select -> decode on one buffer: the score rows are consumed by the select kernel before the decode
+// kernel reuses the buffer for its partials.
+int decode_step_launch(const unique::CacheView& v, const void* d_q, int32_t top_k, float lambda, float sm_scale,
+                       int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out, float* d_lse_out,
+                       float* buf, hipStream_t st) {
+  const int list_len = top_k < v.max_pages_hint ? top_k : v.max_pages_hint;
+  const int stride = score_stride_of(v);
+  hipError_t e = unique::launch_score(v, d_q, lambda, buf, stride, nullptr, refresh_tail != 0, st);
+  if (e != hipSuccess) return hip_fail(e, "page score launch");
+  e = unique::launch_select(v, buf, stride, top_k, d_sel_pages, d_sel_count, st);
+  if (e != hipSuccess) return hip_fail(e, "top-k select launch");
+  e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, top_k, list_len, sm_scale, d_out, d_lse_out, buf, st);
+  return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "sparse decode launch");
 }
 
 }  // namespace
@@ -250,30 +312,30 @@ int unique_decode_step(const unique_cache_desc* desc, const void* d_q, int32_t t
                        int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out,
                        float* d_lse_out, void* d_workspace, size_t workspace_bytes, void* stream) {
   unique::CacheView v;
-  int rc = make_view(desc, &v, true, true);
+  size_t region = 0;
+  int rc = decode_step_check(desc, d_q, top_k, lambda, sm_scale, d_sel_pages, d_sel_count, d_out, &v, &region);
   if (rc != UNIQUE_OK) return rc;
-  if (!d_q || !d_sel_pages || !d_sel_count || !d_out)
-    return fail(UNIQUE_ERR_INVALID_ARG, "d_q, d_sel_pages, d_sel_count and d_out must be non-NULL");
-  if (((uintptr_t)d_q | (uintptr_t)d_out) & 15u)
-    return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_out must be 16-byte aligned");
-  if (top_k < 1) return fail(UNIQUE_ERR_INVALID_ARG, "top_k must be >= 1 (got %d)", top_k);
-  if (!(lambda >= 0.f)) return fail(UNIQUE_ERR_INVALID_ARG, "lambda must be >= 0");
-  if (!(sm_scale == sm_scale)) return fail(UNIQUE_ERR_INVALID_ARG, "sm_scale is NaN");
-  const int list_len = top_k < v.max_pages_hint ? top_k : v.max_pages_hint;
-  size_t region = score_bytes(v);
-  if (decode_bytes(v, list_len) > region) region = decode_bytes(v, list_len);
   rc = check_workspace(d_workspace, workspace_bytes, region);
   if (rc != UNIQUE_OK) return rc;
-  // the score rows are consumed by the select kernel before the decode kernel reuses the buffer for its partials
-  float* buf = reinterpret_cast<float*>(d_workspace);
-  const int stride = score_stride_of(v);
-  hipStream_t st = (hipStream_t)stream;
-  hipError_t e = unique::launch_score(v, d_q, lambda, buf, stride, nullptr, refresh_tail != 0, st);
-  if (e != hipSuccess) return hip_fail(e, "page score launch");
-  e = unique::launch_select(v, buf, stride, top_k, d_sel_pages, d_sel_count, st);
-  if (e != hipSuccess) return hip_fail(e, "top-k select launch");
-  e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, top_k, list_len, sm_scale, d_out, d_lse_out, buf, st);
-  return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "sparse decode launch");
+  return decode_step_launch(v, d_q, top_k, lambda, sm_scale, refresh_tail, d_sel_pages, d_sel_count, d_out, d_lse_out,
+                            reinterpret_cast<float*>(d_workspace), (hipStream_t)stream);
+}
+
+int unique_decode_step_static(const unique_cache_desc* desc, const void* d_q, int32_t top_k, float lambda,
+                              float sm_scale, int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count,
+                              void* d_out, float* d_lse_out, void* stream) {
+  unique::CacheView v;
+  size_t region = 0;
+  int rc = decode_step_check(desc, d_q, top_k, lambda, sm_scale, d_sel_pages, d_sel_count, d_out, &v, &region);
+  if (rc != UNIQUE_OK) return rc;
+  if (region > (size_t)UNIQUE_STATIC_SCRATCH_BYTES)
+    return fail(UNIQUE_ERR_WORKSPACE, "this step needs %zu bytes of scratch, the built-in scratch holds %zu: use "
+                "unique_decode_step with a caller workspace", region, (size_t)UNIQUE_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != UNIQUE_OK) return rc;
+  return decode_step_launch(v, d_q, top_k, lambda, sm_scale, refresh_tail, d_sel_pages, d_sel_count, d_out, d_lse_out,
+                            reinterpret_cast<float*>(ws), (hipStream_t)stream);
 }
 
 int unique_dense_paged_decode(const unique_cache_desc* desc, const void* d_q, float sm_scale, void* d_out,

@@ -72,6 +72,10 @@ class DecodeSession:
         self.lib.decode_step(self.desc, self.wl.q, self.top_k, self.wl.lam if lam is None else lam, sm_scale,
                              refresh_tail, self.sel_pages, self.sel_count, self.out, self.lse, self.workspace)
 
+    def decode_step_static(self, refresh_tail: bool = True, sm_scale: float = 0.0, lam: float | None = None):
+        self.lib.decode_step_static(self.desc, self.wl.q, self.top_k, self.wl.lam if lam is None else lam, sm_scale,
+                                    refresh_tail, self.sel_pages, self.sel_count, self.out, self.lse)
+
     def dense_paged_decode(self, sm_scale: float = 0.0):
         self.lib.dense_paged_decode(self.desc, self.wl.q, sm_scale, self.out_dense, self.lse_dense, self.workspace)
 

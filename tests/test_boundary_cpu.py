@@ -129,6 +129,16 @@ def test_call_argument_validation(lib):
     assert ds(C.byref(d), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, None, None, ws, nws, None) == binding.ERR_INVALID_ARG
     assert ds(C.byref(d), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, 64, None) == binding.ERR_WORKSPACE
     assert ds(C.byref(good_desc(page_stats=0)), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, ws, nws, None) == binding.ERR_INVALID_ARG
+    # the step on the built-in scratch: same validation, and a step that does not fit is refused before any device call
+    dss = c.unique_decode_step_static
+    assert dss(C.byref(d), None, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, None) == binding.ERR_INVALID_ARG
+    assert dss(C.byref(d), 0x7000, 0, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, None) == binding.ERR_INVALID_ARG
+    assert dss(C.byref(d), 0x7000, 4, 0.5, 0.0, 1, None, 0x200, 0x8000, None, None) == binding.ERR_INVALID_ARG
+    assert dss(C.byref(good_desc(page_stats=0)), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, None) == binding.ERR_INVALID_ARG
+    too_big = good_desc(batch=64, max_pages_per_seq=16384)        # 64 x 8 score rows of 16384 floats = 32 MiB
+    assert lib.workspace_bytes(too_big, 4) > binding.STATIC_SCRATCH_BYTES
+    assert dss(C.byref(too_big), 0x7000, 4, 0.5, 0.0, 1, 0x100, 0x200, 0x8000, None, None) == binding.ERR_WORKSPACE
+    assert "built-in scratch" in lib.last_error()
     # dense decode
     h = c.unique_dense_paged_decode
     assert h(C.byref(d), 0x7000, 0.0, None, None, ws, nws, None) == binding.ERR_INVALID_ARG
