@@ -250,6 +250,27 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
 // was loaded (a lane owns a 16-byte chunk of a token's value), and the PV products stay on the
 // vector ALUs. This removes the unpack + FMA + lane-reduction work of the q.k stage, which made the
 // all-VALU kernel issue-bound (VALU busy 67 % on the dense stream).
+// Profiling build (-DUNIQUE_DEC_STAMPS): every wave of the matrix-core kernel records the 100 MHz wall clock at
+// five points into a device array that unique_debug_dec_stamps() hands out; the product build has none of it.
+#ifdef UNIQUE_DEC_STAMPS
+constexpr int kStampSlots = 32, kStampWaves = 1 << 14;
+__device__ unsigned long long g_dec_stamps[kStampWaves][kStampSlots];
+#define DEC_STAMP(slot)                                                                                         \
+  do {                                                                                                          \
+    const int sw_ = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * kDecWaves + wave;          \
+    if (lane == 0 && sw_ < kStampWaves) g_dec_stamps[sw_][slot] = wall_clock64();                               \
+  } while (0)
+// the stamp is taken only once `value` (a 32-bit register) has been produced
+#define DEC_STAMP_AFTER(slot, value)                 \
+  do {                                               \
+    asm volatile("" ::"v"(value) : "memory");        \
+    DEC_STAMP(slot);                                 \
+  } while (0)
+#else
+#define DEC_STAMP(slot) do {} while (0)
+#define DEC_STAMP_AFTER(slot, value) do {} while (0)
+#endif
+
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
@@ -257,7 +278,13 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const Raw16& r) {
   return __builtin_bit_cast(bf16x8_t, r.v);
 }
 
-template <int D, int S, int G>
+#ifndef UNIQUE_DEC_BUFFERS
+#define UNIQUE_DEC_BUFFERS 2
+#endif
+constexpr int kDecBuffers = UNIQUE_DEC_BUFFERS;  // register tiles per wave: one being consumed, the others in flight
+
+// kNT: K and V are read with non-temporal loads (a launch that streams more than the caches hold).
+template <int D, int S, int G, bool kNT>
 __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_kernel(
     CacheView c, const bf16_t* __restrict__ q, const int32_t* __restrict__ sel_pages,
     const int32_t* __restrict__ sel_count, int sel_stride, int pages_per_split, int num_splits, float scale_log2,
@@ -276,6 +303,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
   const int row = b * c.Hkv + hkv;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int begin = split * pages_per_split;
+  DEC_STAMP(0);  // kernel entry
   // the first list entry of this lane is requested together with the lengths (row storage is sel_stride
   // entries long, so the load does not have to wait for the count)
   int first_lp = -1;
@@ -303,11 +331,12 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
   __shared__ float sm_m[kDecWaves][G], sm_l[kDecWaves][G];
 
   // A operand: query head kt (zero rows beyond G), the 8 elements of chunk 4*s + kg
+  const bf16_t* q_row = q + ((int64_t)b * c.H + hkv * G) * D;  // first query row of the group
   bf16x8_t qa[kSteps];
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) {
     Raw16 r = zero_raw();
-    if (kt < G) r = load_raw(q + ((int64_t)b * c.H + hkv * G + kt) * D + (4 * s + kg) * kVec);
+    if (kt < G) r = load_raw(q_row + (int64_t)kt * D + (4 * s + kg) * kVec);
     qa[s] = as_bf16x8(r);
   }
 
@@ -342,41 +371,59 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
     }
     const int n_ent = min(kWave, (end - e0 + kDecWaves - 1) / kDecWaves);
     const int n_tiles = (n_ent * S + kTile - 1) / kTile;
+    DEC_STAMP_AFTER(1, my_phys);  // page ids resolved (list entry and page-table entry arrived)
 
     // slot gs (counted over the wave's entries) -> entry gs / S, token gs % S. Entries at or beyond n_ent
-    // were never looked up and carry ntok = 0.
-    auto slot_info = [&](int gs, int& phys, int& ntok, int& tok) {
-      const int ent = gs / S;
+    // were never looked up and carry ntok = 0; so does every slot of a tile at or beyond n_tiles.
+    auto slot_info = [&](int tile, int slot, int& phys, int& ntok, int& tok) {
+      const int gs = tile * kTile + slot;
       tok = gs % S;
       if constexpr (S >= kTile) {  // one entry per tile: uniform, scalar broadcast
+        const int ent = min(tile / (S / kTile), kWave - 1);
         phys = __builtin_amdgcn_readlane(my_phys, ent);
-        ntok = __builtin_amdgcn_readlane(my_ntok, ent);
+        ntok = tile < n_tiles ? __builtin_amdgcn_readlane(my_ntok, ent) : 0;
       } else {                     // two pages share a tile: per-lane lookup
+        const int ent = min(gs / S, kWave - 1);
         phys = __shfl(my_phys, ent, kWave);
-        ntok = __shfl(my_ntok, ent, kWave);
+        ntok = tile < n_tiles ? __shfl(my_ntok, ent, kWave) : 0;
       }
     };
 
-    // Three register buffers: while tile i is consumed, the loads of tiles i+1 and i+2 are in flight, so a
-    // wave is not paced by one memory round trip per tile. The loop is unrolled by three so that buffer
-    // roles are static (no register copies, and the waits only cover the oldest tile).
-    Raw16 kb0[kSteps], vb0[kVLoads], kb1[kSteps], vb1[kVLoads], kb2[kSteps], vb2[kVLoads];
-    bool kv0 = false, kv1 = false, kv2 = false;
+    // kDecBuffers register tiles: while one is consumed, the loads of the following kDecBuffers - 1 are in flight,
+    // so a wave is not paced by one memory round trip per tile. Every load is issued unconditionally -- a slot
+    // that has no token (beyond a partial page, an invalid list entry, a tile past the wave's last) reads the
+    // group's first query row instead, which is always cached, finite and never attended (its probability is
+    // zero) -- so the pipeline is straight-line code and every wait names exactly the requests that may stay in
+    // flight; with predicated loads the compiler waited for ALL outstanding loads before each tile, prefetched
+    // ones included. Slots beyond a sequence's length are still never read.
+    Raw16 kb[kDecBuffers][kSteps], vb[kDecBuffers][kVLoads];
+    bool kv[kDecBuffers];
     auto issue = [&](int tile, Raw16(&kd)[kSteps], Raw16(&vd)[kVLoads], bool& kvalid) {
       int phys, ntok, tok;
-      slot_info(tile * kTile + kt, phys, ntok, tok);
+      slot_info(tile, kt, phys, ntok, tok);
       kvalid = tok < ntok;
-      const bf16_t* kp = kc + phys * page_stride + head_off + (int64_t)tok * D + kg * kVec;
+      const bf16_t* kp = kvalid ? kc + phys * page_stride + head_off + (int64_t)tok * D + kg * kVec : q_row;
 #pragma unroll
-      for (int s = 0; s < kSteps; ++s) kd[s] = kvalid ? load_raw_stream(kp + s * (4 * kVec), c.stream_nt) : zero_raw();
+      for (int s = 0; s < kSteps; ++s) kd[s] = load_raw_stream(kp + s * (4 * kVec), kNT);
 #pragma unroll
       for (int j = 0; j < kVLoads; ++j) {
-        slot_info(tile * kTile + j * kTokPerLoad + vr_, phys, ntok, tok);
-        const bf16_t* vp = vc + phys * page_stride + head_off + (int64_t)tok * D + vc_ * kVec;
-        vd[j] = tok < ntok ? load_raw_stream(vp, c.stream_nt) : zero_raw();
+        slot_info(tile, j * kTokPerLoad + vr_, phys, ntok, tok);
+        const bf16_t* vp = tok < ntok ? vc + phys * page_stride + head_off + (int64_t)tok * D + vc_ * kVec : q_row;
+        vd[j] = load_raw_stream(vp, kNT);
       }
     };
     auto consume = [&](const Raw16(&kr)[kSteps], const Raw16(&vr)[kVLoads], bool kvalid_cur) {
+#ifdef UNIQUE_DEC_EXPERIMENT_NO_COMPUTE   // timing experiment only (wrong results): the loads with a trivial consumer
+      {
+        uint32_t x = 0;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) x ^= kr[s].v.x ^ kr[s].v.y ^ kr[s].v.z ^ kr[s].v.w;
+#pragma unroll
+        for (int j = 0; j < kVLoads; ++j) x ^= vr[j].v.x ^ vr[j].v.y ^ vr[j].v.z ^ vr[j].v.w;
+        acc[0][0] += __uint_as_float(x & 0x3fffffffu) * (kvalid_cur ? 1.f : 0.f);
+        return;
+      }
+#endif
       f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < kSteps; ++s)
@@ -426,20 +473,29 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       __builtin_amdgcn_wave_barrier();
     };
 
-    issue(0, kb0, vb0, kv0);
-    if (n_tiles > 1) issue(1, kb1, vb1, kv1);
-    for (int tile = 0; tile < n_tiles; tile += 3) {
-      if (tile + 2 < n_tiles) issue(tile + 2, kb2, vb2, kv2);
-      consume(kb0, vb0, kv0);
-      if (tile + 1 >= n_tiles) break;
-      if (tile + 3 < n_tiles) issue(tile + 3, kb0, vb0, kv0);
-      consume(kb1, vb1, kv1);
-      if (tile + 2 >= n_tiles) break;
-      if (tile + 4 < n_tiles) issue(tile + 4, kb1, vb1, kv1);
-      consume(kb2, vb2, kv2);
+#pragma unroll
+    for (int u = 0; u < kDecBuffers - 1; ++u) issue(u, kb[u], vb[u], kv[u]);
+    for (int t0 = 0; t0 < n_tiles; t0 += kDecBuffers) {
+#pragma unroll
+      for (int u = 0; u < kDecBuffers; ++u) {
+        constexpr int kAhead = kDecBuffers - 1;
+        issue(t0 + u + kAhead, kb[(u + kAhead) % kDecBuffers], vb[(u + kAhead) % kDecBuffers], kv[(u + kAhead) % kDecBuffers]);
+        if (u == 0 || t0 + u < n_tiles) consume(kb[u], vb[u], kv[u]);  // uniform
+        if (t0 + u == 0) DEC_STAMP_AFTER(2, acc[0][0]);  // first tile consumed (first K/V data arrived)
+#ifdef UNIQUE_DEC_STAMPS
+        if (t0 + u < n_tiles && t0 + u < kStampSlots - 6) DEC_STAMP_AFTER(6 + t0 + u, acc[0][0]);  // tile t0 + u consumed
+        if (t0 + u == 0) {  // which compute unit this wave runs on (HW_ID: bits 8-11 CU, 13-15 SE; XCC_ID register)
+          const int sw_ = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * kDecWaves + wave;
+          if (lane == 0 && sw_ < kStampWaves)
+            g_dec_stamps[sw_][5] = ((unsigned long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) << 32) |
+                                   (unsigned)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11));
+        }
+#endif
+      }
     }
   }
 
+  DEC_STAMP_AFTER(3, acc[0][0]);  // streaming loop done
   // the wave's result: sum the per-lane l over the 16 token lanes, and acc over the token rows of the V layout
 #pragma unroll
   for (int i = 0; i < 4; ++i) l[i] = group_allreduce<16>(l[i], OpSum());
@@ -483,6 +539,7 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       }
     }
   }
+  DEC_STAMP(4);  // partial results stored
 }
 
 // Log-sum-exp merge of the chunk partials of one (sequence, query head); writes out (and lse).
@@ -561,11 +618,15 @@ hipError_t launch_t(const CacheView& cv, const void* q, const int32_t* sel, cons
   float* part_ml = partials + (size_t)rows * plan.num_splits * G * D;
   const float scale_log2 = (sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)D)) * kLog2e;
 #ifndef UNIQUE_DEC_NO_MFMA
-  if constexpr (sizeof(T) == 2)
-    paged_decode_partial_mfma_kernel<D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
-        c, reinterpret_cast<const bf16_t*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
-        part_o, part_ml, reinterpret_cast<bf16_t*>(out), lse);
-  else
+  if constexpr (sizeof(T) == 2) {
+    auto go = [&](auto kernel) {
+      kernel<<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
+          c, reinterpret_cast<const bf16_t*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits,
+          scale_log2, part_o, part_ml, reinterpret_cast<bf16_t*>(out), lse);
+    };
+    if (c.stream_nt) go(paged_decode_partial_mfma_kernel<D, S, G, true>);
+    else go(paged_decode_partial_mfma_kernel<D, S, G, false>);
+  } else
 #endif
     paged_decode_partial_kernel<T, D, S, G><<<dim3(plan.num_splits, c.Hkv, c.B), dim3(kDecWaves * kWave), 0, st>>>(
         c, reinterpret_cast<const T*>(q), sel, cnt, sel_stride, plan.pages_per_split, plan.num_splits, scale_log2,
@@ -602,6 +663,14 @@ hipError_t dispatch_s(const CacheView& c, const void* q, const int32_t* sel, con
 }
 
 }  // namespace
+
+#ifdef UNIQUE_DEC_STAMPS
+extern "C" int unique_debug_dec_stamps(void** ptr, int* waves, int* slots) {
+  *waves = kStampWaves;
+  *slots = kStampSlots;
+  return (int)hipGetSymbolAddress(ptr, HIP_SYMBOL(g_dec_stamps));
+}
+#endif
 
 bool decode_supported(int dtype, int D, int S, int G) {
   return (dtype == 0 || dtype == 1) && (D == 64 || D == 128) && (S == 8 || S == 16 || S == 32) &&
