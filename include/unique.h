@@ -156,7 +156,9 @@ int unique_select_topk(const unique_cache_desc* desc, const float* d_scores, int
  *                 LOGICAL page indices (any order, distinct); d_sel_count : int32 [batch][H_kv]
  *                 entries used per row (<= sel_stride). Entries that are negative or not a page of
  *                 the sequence are skipped.
- *   sel_stride  : host upper bound on d_sel_count[] and the row stride of d_sel_pages.
+ *   sel_stride  : host upper bound on d_sel_count[] and the row stride of d_sel_pages; every one of the first
+ *                 d_sel_count entries of a row is visited, also when sel_stride exceeds the pages of the
+ *                 sequences. The workspace needs unique_workspace_bytes(desc, sel_stride).
  *   sm_scale    : logit scale; <= 0 selects 1/sqrt(D).
  *   d_out       : [batch][H][D] dtype.  d_lse_out : optional float [batch][H], natural-log
  *                 sum-exp of the scaled logits (-inf and a zero output row if no token was attended). */

@@ -162,9 +162,9 @@ int decode_step_check(const unique_cache_desc* desc, const void* d_q, int32_t to
   if (top_k < 1) return fail(UNIQUE_ERR_INVALID_ARG, "top_k must be >= 1 (got %d)", top_k);
   if (!(lambda >= 0.f)) return fail(UNIQUE_ERR_INVALID_ARG, "lambda must be >= 0");
   if (!(sm_scale == sm_scale)) return fail(UNIQUE_ERR_INVALID_ARG, "sm_scale is NaN");
-  const int list_len = top_k < v->max_pages_hint ? top_k : v->max_pages_hint;
+  // the decode part is planned like unique_sparse_paged_decode with sel_stride = top_k (same chunks, same bits)
   *region = score_bytes(*v);
-  if (decode_bytes(*v, list_len) > *region) *region = decode_bytes(*v, list_len);
+  if (decode_bytes(*v, top_k) > *region) *region = decode_bytes(*v, top_k);
   return UNIQUE_OK;
 }
 
@@ -173,13 +173,12 @@ int decode_step_check(const unique_cache_desc* desc, const void* d_q, int32_t to
 int decode_step_launch(const unique::CacheView& v, const void* d_q, int32_t top_k, float lambda, float sm_scale,
                        int32_t refresh_tail, int32_t* d_sel_pages, int32_t* d_sel_count, void* d_out, float* d_lse_out,
                        float* buf, hipStream_t st) {
-  const int list_len = top_k < v.max_pages_hint ? top_k : v.max_pages_hint;
   const int stride = score_stride_of(v);
   hipError_t e = unique::launch_score(v, d_q, lambda, buf, stride, nullptr, refresh_tail != 0, st);
   if (e != hipSuccess) return hip_fail(e, "page score launch");
   e = unique::launch_select(v, buf, stride, top_k, d_sel_pages, d_sel_count, st);
   if (e != hipSuccess) return hip_fail(e, "top-k select launch");
-  e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, top_k, list_len, sm_scale, d_out, d_lse_out, buf, st);
+  e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, top_k, top_k, sm_scale, d_out, d_lse_out, buf, st);
   return e == hipSuccess ? UNIQUE_OK : hip_fail(e, "sparse decode launch");
 }
 
@@ -203,9 +202,9 @@ int unique_workspace_bytes(const unique_cache_desc* desc, int32_t top_k, size_t*
   unique::CacheView v;
   const int rc = make_view(&d, &v, false, false);
   if (rc != UNIQUE_OK) return rc;
-  const int sparse_len = top_k < v.max_pages_hint ? top_k : v.max_pages_hint;
+  // a caller's list for unique_sparse_paged_decode may be up to top_k entries long whatever the sequence lengths
   size_t need = score_bytes(v);
-  const size_t sp = decode_bytes(v, sparse_len), de = decode_bytes(v, v.max_pages_hint);
+  const size_t sp = decode_bytes(v, top_k), de = decode_bytes(v, v.max_pages_hint);
   if (sp > need) need = sp;
   if (de > need) need = de;
   *out_bytes = round_up(need, kAlign);
@@ -300,7 +299,9 @@ int unique_sparse_paged_decode(const unique_cache_desc* desc, const void* d_q, c
     return fail(UNIQUE_ERR_INVALID_ARG, "d_q and d_out must be 16-byte aligned");
   if (sel_stride < 1) return fail(UNIQUE_ERR_INVALID_ARG, "sel_stride must be >= 1 (got %d)", sel_stride);
   if (!(sm_scale == sm_scale)) return fail(UNIQUE_ERR_INVALID_ARG, "sm_scale is NaN");
-  const int list_len = sel_stride < v.max_pages_hint ? sel_stride : v.max_pages_hint;
+  // the split plan covers every entry a row may hold (sel_count <= sel_stride), also when the list is longer than
+  // the sequences have pages (padding or foreign entries in between are skipped, valid ones behind them are not lost)
+  const int list_len = sel_stride;
   rc = check_workspace(d_workspace, workspace_bytes, decode_bytes(v, list_len));
   if (rc != UNIQUE_OK) return rc;
   const hipError_t e = unique::launch_decode(v, d_q, d_sel_pages, d_sel_count, sel_stride, list_len, sm_scale, d_out,

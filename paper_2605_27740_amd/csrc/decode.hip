@@ -678,7 +678,9 @@ bool decode_supported(int dtype, int D, int S, int G) {
 }
 
 SplitPlan plan_splits(int rows, int max_list_len) {
-  // aim at ~4 workgroups (16 waves) per CU of a 256-CU device, with at least 2 pages per wave
+  // aim at ~2 workgroups (8 waves) per CU of a 256-CU device, with at least 1 page per wave; from 256 rows on one
+  // workgroup per row already fills the device, the row is not cut and no merge launch is needed (lists of up to
+  // UNIQUE_DEC_MAX_PPS pages)
 #ifndef UNIQUE_DEC_TARGET_GROUPS
 #define UNIQUE_DEC_TARGET_GROUPS 512
 #endif
@@ -688,10 +690,10 @@ SplitPlan plan_splits(int rows, int max_list_len) {
 #endif
   if (rows < 1) rows = 1;
   if (max_list_len < 1) max_list_len = 1;
-  const int wanted = (kTargetGroups + rows - 1) / rows;
+  const int wanted = rows >= 256 ? 1 : (kTargetGroups + rows - 1) / rows;
   int pps = (max_list_len + wanted - 1) / wanted;
 #ifndef UNIQUE_DEC_MIN_PAGES_PER_WAVE
-#define UNIQUE_DEC_MIN_PAGES_PER_WAVE 2
+#define UNIQUE_DEC_MIN_PAGES_PER_WAVE 1
 #endif
   if (pps < UNIQUE_DEC_MIN_PAGES_PER_WAVE * kDecWaves) pps = UNIQUE_DEC_MIN_PAGES_PER_WAVE * kDecWaves;
   // long lists are cut into many equal chunks so that ragged batches balance across the CUs

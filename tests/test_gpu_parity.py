@@ -571,6 +571,29 @@ def test_invalid_list_entries_are_skipped(gpu_lib):
     assert (sess.out == 0).all() and torch.isinf(sess.lse).all() and (sess.lse < 0).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_a_list_longer_than_the_sequence_is_walked_to_its_end(gpu_lib, dtype):
+    """sel_stride (and sel_count) may exceed the number of pages of the sequences: padding and foreign entries are
+    skipped, and valid entries that sit behind them, beyond the sequence's page count, are still attended."""
+    wl = W.build("longlist", 47, dtype=dtype, B=2, H=8, Hkv=2, D=64, S=16, seq_lens=[20 * 16 - 3, 9 * 16], top_k=4,
+                 key_mode="shift", plant_mode="one_percent", permute=True).to(DEV)
+    stride = 1000                                    # 50 times the pages of the longer sequence
+    sess = DecodeSession(wl, top_k=stride)
+    sel = torch.full((wl.B, wl.Hkv, stride), -1, device=DEV, dtype=torch.int32)
+    sel[:, :, 1::7] = 10 ** 6                        # foreign entries in between
+    want = {(0, 0): [19, 3], (0, 1): [0], (1, 0): [8, 7, 1], (1, 1): [5]}
+    for (b, h), pages in want.items():
+        for i, pg in enumerate(pages):
+            sel[b, h, stride - 1 - 211 * i] = pg     # valid entries far behind the sequence's page count
+    cnt = torch.full((wl.B, wl.Hkv), stride, device=DEV, dtype=torch.int32)
+    sess.sparse_paged_decode(sel_pages=sel, sel_count=cnt)
+    torch.cuda.synchronize()
+    oc, q = Hn.oracle_cache(wl)
+    for (b, h), pages in want.items():
+        for g in range(wl.G):
+            Hn.check_attention_head(sess.out, sess.lse, oc, q, b, h * wl.G + g, np.array(pages, np.int32), wl.dtype)
+
+
 @pytest.mark.parametrize("list_len", [6, 700])
 def test_empty_and_all_invalid_lists_bf16(gpu_lib, list_len):
     """bf16 caches (matrix-core kernel), a list short enough for one chunk per row (the partial kernel writes the
