@@ -40,6 +40,11 @@ def parse():
                     help="time the step as update_page_stats + score_select_topk + sparse_paged_decode instead of unique_decode_step")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="microbenchmarks at the shapes of the paper's Appendix A / B tables instead of a decode step")
+    ap.add_argument("--phase-stamps", action="store_true",
+                    help="profiling build: per-wave wall-clock stamps inside the sparse decode kernel of a cold decode step")
+    ap.add_argument("--gather-probe", action="store_true",
+                    help="profiling build: the bare K/V gather of the sparse decode (no page table, no arithmetic) at the "
+                         "128K batch's shape, for several chunk placements, load patterns and prefetch depths")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="only run a device-to-device copy of this many bytes (counter calibration for rocprofv3 --pmc)")
     return ap.parse_args()
@@ -108,8 +113,7 @@ def kernel_trace(torch, fn, n):
     """Durations of the individual kernels inside the library calls (the split-K partial kernel apart from the
     merge), from the device timestamps torch's profiler collects; None if the profiler is not usable here (for
     instance when the whole program already runs under rocprofv3)."""
-    if any(k in os.environ for k in ("ROCPROFILER_LIBRARY_CTOR", "ROCP_TOOL_LIBRARIES", "ROCPROF_OUTPUT_PATH")) or \
-            "rocprof" in os.environ.get("LD_PRELOAD", ""):
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
         return None
     try:
         from torch.profiler import ProfilerActivity, profile
@@ -158,6 +162,9 @@ def main():
 
     if args.paper_shapes:
         paper_shapes(dev)
+        return
+    if args.phase_stamps or args.gather_probe:
+        (phase_stamps if args.phase_stamps else gather_probe)(args, dev)
         return
     stats_dtype = torch.bfloat16 if args.stats_dtype == "bf16" else torch.float32
 
@@ -425,6 +432,113 @@ def main():
         "paper_context": "paper: 11.4x attention-path speedup over dense FlashInfer at 32K, >=5.3x end to end (1x H100, S=8, batch 80)",
     }
     print(json.dumps(line))
+
+
+def _profiling_library():
+    import ctypes as C
+    from paper_2605_27740_amd import binding, build
+    path = build.PROF_LIB_PATH if os.path.exists(build.PROF_LIB_PATH) else build.build_profiling_library()
+    return binding.Library(path), C.CDLL("libamdhip64.so"), C
+
+
+def _device_kernel_us(torch, fn, n, name):
+    """median device duration (us) of the kernels whose name contains `name` over n calls of fn(i)"""
+    from torch.profiler import ProfilerActivity, profile
+    with profile(activities=[ProfilerActivity.CUDA]) as prof:
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+    xs = sorted(float(ev.device_time) for ev in prof.events() if name in ev.name)
+    return xs[len(xs) // 2] if xs else float("nan")
+
+
+def phase_stamps(args, dev):
+    """Where the time of the sparse decode kernel goes: every wave of the profiling build stamps the 100 MHz wall
+    clock at entry, once its page ids are resolved, after its first tile, at the end of its loop, after its stores
+    and after every tile. Cold decode steps (Flusher), 10 launches after 2 untimed ones. Prints one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2605_27740_amd import workloads as W
+    from paper_2605_27740_amd.session import DecodeSession
+    lib, hip, C = _profiling_library()
+    kw = {} if args.top_k is None else {"top_k": args.top_k}
+    wl = {"c2": W.config2, "c3": W.config3, "c4": W.config4, "c5": W.config5}[args.workload](device=dev, **kw)
+    sess = DecodeSession(wl, want_scores=False, lib=lib,
+                         stats_dtype=torch.bfloat16 if args.stats_dtype == "bf16" else torch.float32)
+    sess.update_page_stats()
+    ptr, waves, slots = C.c_void_p(), C.c_int(), C.c_int()
+    assert lib.c.unique_debug_dec_stamps(C.byref(ptr), C.byref(waves), C.byref(slots)) == 0
+    nbytes = waves.value * slots.value * 8
+    flusher = Flusher(torch, wl, dev)
+    runs, tiles = [], []
+    for it in range(12):
+        torch.cuda.synchronize()
+        assert hip.hipMemset(ptr, 0, C.c_size_t(nbytes)) == 0
+        flusher.before_step(it)
+        sess.decode_step(refresh_tail=True)
+        torch.cuda.synchronize()
+        host = np.zeros((waves.value, slots.value), np.uint64)
+        assert hip.hipMemcpy(C.c_void_p(host.ctypes.data), ptr, C.c_size_t(nbytes), 2) == 0
+        live = host[host[:, 0] > 0].astype(np.int64)
+        if it < 2:
+            continue
+        t0 = live[:, 0].min()
+        runs.append((live[:, :5] - t0) / 100.0)                       # us since the first wave entered
+        tl = live[:, 6:]
+        tiles.append(np.where(tl > 0, (tl - t0) / 100.0, np.nan))
+    r, tl = np.stack(runs), np.stack(tiles)
+    q = lambda x: [round(float(v), 2) for v in np.percentile(x, [0, 10, 50, 90, 100])]
+    names = ["entry", "page_ids_resolved", "first_tile_done", "loop_done", "partials_stored"]
+    edges = np.arange(0, 2 * (int(np.nanmax(r[:, :, 4]) // 2) + 2), 2.0)
+    hist = sum(np.histogram(t[np.isfinite(t)], bins=edges)[0] for t in tl) / tl.shape[0]
+    tile_bytes = 2 * 16 * wl.D * wl.k_cache.element_size()             # one 16-token tile of K and of V
+    print(json.dumps({
+        "phase_stamps": {"workload": wl.name, "top_k_pages": sess.top_k, "waves": int(r.shape[1]), "launches": int(r.shape[0]),
+                         "percentiles": "min, p10, median, p90, max over waves and launches, us since the first wave entered",
+                         "stamps_us": {n: q(r[:, :, i]) for i, n in enumerate(names)},
+                         "phase_lengths_us": {f"{names[i]}->{names[i + 1]}": q(r[:, :, i + 1] - r[:, :, i]) for i in range(4)},
+                         "kernel_span_us_per_launch": [round(float(x), 2) for x in r[:, :, 4].max(axis=1)],
+                         "consumed_TBps_per_2us_bin": {str(int(e)): round(float(h) * tile_bytes / 2e-6 / 1e12, 2)
+                                                       for e, h in zip(edges[:-1], hist)}}}))
+
+
+def gather_probe(args, dev):
+    """The bare memory access of the sparse decode at the 128K batch's shape (128 rows x 256 tiles of 4 KiB K + 4 KiB V
+    out of two 4.3 GB pools), kernel durations from the device timestamps, eight different lists in turn (cold)."""
+    import torch
+    lib, hip, C = _profiling_library()
+    rows, k, heads, pool = 128, 256, 8, 131072
+    kpool = torch.empty((pool, heads, 2048), dtype=torch.bfloat16, device=dev).fill_(1.0)
+    vpool = torch.empty((pool, heads, 2048), dtype=torch.bfloat16, device=dev).fill_(2.0)
+    sink = torch.zeros((4096,), dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu"); g.manual_seed(7)
+    lists = {"random_4KiB_chunks": [], "consecutive_pages": [], "random_32KiB_chunks(all heads of a sequence pick the same pages)": []}
+    for l in range(8):
+        rnd = torch.sort(torch.randint(0, pool, (rows, k), generator=g), dim=1).values
+        lists["random_4KiB_chunks"].append(rnd.to(torch.int32).to(dev))
+        start = (torch.arange(rows) // heads) * 8192 + (l * 997) % 7000
+        lists["consecutive_pages"].append((start[:, None] + torch.arange(k)[None, :]).to(torch.int32).to(dev))
+        lists["random_32KiB_chunks(all heads of a sequence pick the same pages)"].append(
+            rnd[(torch.arange(rows) // heads) * heads].to(torch.int32).to(dev))
+    out, nbytes = [], rows * k * 8192
+    fn = lib.c.unique_debug_gather_probe
+    fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 7 + [C.c_void_p, C.c_void_p]
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    for place, ls in lists.items():
+        for pattern in (0, 1):
+            for depth in (2, 4):
+                for waves, ppw in ((4, 64), (4, 128), (8, 128), (4, 256)):
+                    def call(i):
+                        rc = fn(kpool.data_ptr(), vpool.data_ptr(), ls[i % 8].data_ptr(), rows, k, heads, ppw, waves, depth,
+                                pattern, sink.data_ptr(), stream)
+                        assert rc == 0, rc
+                    call(0); torch.cuda.synchronize()
+                    us = _device_kernel_us(torch, call, 16, "gather_probe_kernel")
+                    out.append({"placement": place, "k_load_pattern": "contiguous_1KiB" if pattern == 0 else "mfma_operand_64B_x16",
+                                "tiles_in_flight": depth, "waves_per_wg": waves, "pages_per_wg": ppw,
+                                "workgroups": rows * ((k + ppw - 1) // ppw), "us": round(us, 2),
+                                "TBps": round(nbytes / us / 1e6, 3)})
+    print(json.dumps({"gather_probe": {"bytes": nbytes, "rows": rows, "pages_per_row": k, "results": out}}))
 
 
 def paper_shapes(dev):

@@ -49,8 +49,32 @@ def build_library(force: bool = False, extra_flags: list[str] | None = None, job
     return LIB_PATH
 
 
+PROF_LIB_PATH = os.path.join(HERE, "libunique_gfx950_prof.so")
+
+
+def build_profiling_library(force: bool = False) -> str:
+    """The profiling build: the product objects with decode.hip recompiled under -DUNIQUE_DEC_STAMPS (per-wave
+    wall-clock stamps in the sparse decode kernel, the bare gather probe). Used by bench.py --phase-stamps and
+    --gather-probe only."""
+    build_library()
+    if not force and os.path.exists(PROF_LIB_PATH) and os.path.getmtime(PROF_LIB_PATH) >= _deps_mtime():
+        return PROF_LIB_PATH
+    obj = os.path.join(OBJ_DIR, "decode_prof.o")
+    cmd = [HIPCC, *FLAGS, "-DUNIQUE_DEC_STAMPS", "-c", os.path.join(CSRC, "decode.hip"), "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for the profiling build of decode.hip:\n{r.stderr}")
+    objs = [obj] + [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES if s != "decode.hip"]
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROF_LIB_PATH, *objs],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stderr}")
+    return PROF_LIB_PATH
+
+
 if __name__ == "__main__":
     print(build_library(force=True))
+    print(build_profiling_library(force=True))
 
 
 C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "gpu_client.c")

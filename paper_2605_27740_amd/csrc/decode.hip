@@ -250,8 +250,11 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_kernel(
 // was loaded (a lane owns a 16-byte chunk of a token's value), and the PV products stay on the
 // vector ALUs. This removes the unpack + FMA + lane-reduction work of the q.k stage, which made the
 // all-VALU kernel issue-bound (VALU busy 67 % on the dense stream).
-// Profiling build (-DUNIQUE_DEC_STAMPS): every wave of the matrix-core kernel records the 100 MHz wall clock at
-// five points into a device array that unique_debug_dec_stamps() hands out; the product build has none of it.
+// Profiling build (-DUNIQUE_DEC_STAMPS, a second library next to the product one): every wave of the matrix-core
+// kernel records the 100 MHz wall clock at kernel entry, once its page ids are resolved, after its first tile, at
+// the end of its loop and after its stores, after every tile, and the compute unit it ran on, into a device array
+// that unique_debug_dec_stamps() hands out; unique_debug_gather_probe() (bottom of this file) is the bare memory
+// access of the kernel. The product build has none of it.
 #ifdef UNIQUE_DEC_STAMPS
 constexpr int kStampSlots = 32, kStampWaves = 1 << 14;
 __device__ unsigned long long g_dec_stamps[kStampWaves][kStampSlots];
@@ -669,6 +672,72 @@ extern "C" int unique_debug_dec_stamps(void** ptr, int* waves, int* slots) {
   *waves = kStampWaves;
   *slots = kStampSlots;
   return (int)hipGetSymbolAddress(ptr, HIP_SYMBOL(g_dec_stamps));
+}
+
+// Ceiling probe of the profiling build: the memory access of the sparse decode with everything else taken away.
+// One wave fetches the 4 KiB K tile and the 4 KiB V tile of each of its (physical page, head) entries -- page ids
+// straight from `list`, no page table, no arithmetic but an xor -- with kDepth tiles in flight. kPattern 0: every
+// load instruction covers a contiguous 1 KiB; 1: K in the operand layout of the matrix-core q.k stage (64-byte
+// pieces of 16 rows). Geometry as the decode kernel: rows x ceil(k / pages_per_wg) workgroups of `waves` waves.
+namespace {
+typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));
+template <int kPattern, int kDepth>
+__global__ __launch_bounds__(1024) void gather_probe_kernel(const char* __restrict__ kpool, const char* __restrict__ vpool,
+                                                             const int32_t* __restrict__ list, int k, int pages_per_wg,
+                                                             int waves, int heads, probe_u32x4* __restrict__ sink) {
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
+  const int begin = split * pages_per_wg, end = min(begin + pages_per_wg, k);
+  const int hkv = row % heads;
+  const int n = min(kWave, (end - begin - wave + waves - 1) / waves);  // entries of this wave (lane i holds the i-th)
+  int my_phys = 0;
+  if (lane < n) my_phys = list[(size_t)row * k + begin + wave + lane * waves];
+  probe_u32x4 acc = {0, 0, 0, 0};
+  probe_u32x4 buf[kDepth][8];
+  const int koff = kPattern == 0 ? lane * 16 : (lane % 16) * 256 + (lane / 16) * 16;
+  const int kstep = kPattern == 0 ? 1024 : 64;
+  auto issue = [&](int i, probe_u32x4(&b)[8]) {  // past the wave's last entry: its last page again (keeps the code straight-line)
+    const int phys = __builtin_amdgcn_readlane(my_phys, max(min(i, n - 1), 0));
+    const size_t base = ((size_t)phys * heads + hkv) * 4096;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      b[j] = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4*>(kpool + base + koff + j * kstep));
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      b[4 + j] = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4*>(vpool + base + lane * 16 + j * 1024));
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth; ++d) issue(d, buf[d]);
+  for (int i = 0; i < n; i += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc ^= buf[d][j];
+      issue(i + d + kDepth, buf[d]);
+    }
+  }
+  if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) sink[threadIdx.x] = acc;  // never true in practice; keeps the loads alive
+}
+}  // namespace
+
+// k_pool / v_pool: [num_pages][heads][4096 bytes]; list: int32 [rows][k] physical page ids (all < num_pages, which the
+// caller guarantees); sink: 16 KiB of device memory. Returns a hipError_t.
+extern "C" int unique_debug_gather_probe(const void* k_pool, const void* v_pool, const int32_t* list, int rows, int k,
+                                         int heads, int pages_per_wg, int waves, int depth, int pattern, void* sink,
+                                         void* stream) {
+  if (rows < 1 || k < 1 || heads < 1 || waves < 1 || waves > 16 || pages_per_wg < waves || pages_per_wg > 64 * waves)
+    return (int)hipErrorInvalidValue;
+  const dim3 grid((k + pages_per_wg - 1) / pages_per_wg, rows), block(waves * kWave);
+  auto go = [&](auto kernel) {
+    kernel<<<grid, block, 0, (hipStream_t)stream>>>((const char*)k_pool, (const char*)v_pool, list, k, pages_per_wg,
+                                                    waves, heads, (probe_u32x4*)sink);
+  };
+  if (pattern == 0 && depth == 2) go(gather_probe_kernel<0, 2>);
+  else if (pattern == 0 && depth == 4) go(gather_probe_kernel<0, 4>);
+  else if (pattern == 1 && depth == 2) go(gather_probe_kernel<1, 2>);
+  else if (pattern == 1 && depth == 4) go(gather_probe_kernel<1, 4>);
+  else return (int)hipErrorInvalidValue;
+  return (int)hipGetLastError();
 }
 #endif
 
