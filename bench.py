@@ -486,7 +486,19 @@ def phase_stamps(args, dev):
         runs.append((live[:, :5] - t0) / 100.0)                       # us since the first wave entered
         tl = live[:, 6:]
         tiles.append(np.where(tl > 0, (tl - t0) / 100.0, np.nan))
+        hw = live[:, 5]          # slot 5: HW_ID register in the high word (compute unit: bits 8-11, shader engine: 13-15), XCC id in the low
     r, tl = np.stack(runs), np.stack(tiles)
+    xcc, se, cu = hw & 0xF, (hw >> 45) & 0x7, (hw >> 40) & 0xF
+    done = r[:, :, 3].mean(axis=0)
+    by = lambda key: {str(int(v)): round(float(done[key == v].mean()), 2) for v in np.unique(key)}
+    idx = np.arange(done.shape[0])
+    wave_in_wg, wg = idx % 4, idx // 4
+    seq = wg // (4 * wl.Hkv)                                   # grid (splits, Hkv, B): the sequence is the slowest index
+    tm = np.nanmean(tl, axis=0)                                  # [waves, tiles]: mean time at which each tile was consumed
+    tiles_of = lambda b_: [round(float(x), 1) for x in np.nanmean(tm[seq == b_], axis=0) if np.isfinite(x)]
+    first_tile = r[:, :, 2].mean(axis=0)
+    same_list = float(np.corrcoef(r[0, :, 3], r[4, :, 3])[0, 1])      # launches 0 and 4 use the same query set
+    other_list = float(np.corrcoef(r[0, :, 3], r[1, :, 3])[0, 1])
     q = lambda x: [round(float(v), 2) for v in np.percentile(x, [0, 10, 50, 90, 100])]
     names = ["entry", "page_ids_resolved", "first_tile_done", "loop_done", "partials_stored"]
     edges = np.arange(0, 2 * (int(np.nanmax(r[:, :, 4]) // 2) + 2), 2.0)
@@ -498,6 +510,13 @@ def phase_stamps(args, dev):
                          "stamps_us": {n: q(r[:, :, i]) for i, n in enumerate(names)},
                          "phase_lengths_us": {f"{names[i]}->{names[i + 1]}": q(r[:, :, i + 1] - r[:, :, i]) for i in range(4)},
                          "kernel_span_us_per_launch": [round(float(x), 2) for x in r[:, :, 4].max(axis=1)],
+                         "loop_done_us_mean_by_xcc": by(xcc), "loop_done_us_mean_by_shader_engine": by(se),
+                         "loop_done_us_mean_by_cu_in_engine": by(cu), "compute_units_seen": int(len(np.unique(xcc * 4096 + se * 16 + cu))),
+                         "loop_done_us_mean_by_sequence": by(seq),
+                         "tile_done_us_first_sequence": tiles_of(0), "tile_done_us_last_sequence": tiles_of(int(seq.max())),
+                         "correlation_first_tile_done_vs_loop_done": round(float(np.corrcoef(first_tile, done)[0, 1]), 3),
+                         "loop_done_correlation_between_launches": {"same_page_lists": round(same_list, 3),
+                                                                    "different_page_lists": round(other_list, 3)},
                          "consumed_TBps_per_2us_bin": {str(int(e)): round(float(h) * tile_bytes / 2e-6 / 1e12, 2)
                                                        for e, h in zip(edges[:-1], hist)}}}))
 
@@ -525,16 +544,18 @@ def gather_probe(args, dev):
     fn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 7 + [C.c_void_p, C.c_void_p]
     stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
     for place, ls in lists.items():
-        for pattern in (0, 1):
+        for pattern in (0, 1, 2):
             for depth in (2, 4):
                 for waves, ppw in ((4, 64), (4, 128), (8, 128), (4, 256)):
+                    if pattern == 2 and waves * depth * 8192 > 160 * 1024:
+                        continue
                     def call(i):
                         rc = fn(kpool.data_ptr(), vpool.data_ptr(), ls[i % 8].data_ptr(), rows, k, heads, ppw, waves, depth,
                                 pattern, sink.data_ptr(), stream)
                         assert rc == 0, rc
                     call(0); torch.cuda.synchronize()
-                    us = _device_kernel_us(torch, call, 16, "gather_probe_kernel")
-                    out.append({"placement": place, "k_load_pattern": "contiguous_1KiB" if pattern == 0 else "mfma_operand_64B_x16",
+                    us = _device_kernel_us(torch, call, 16, "gather_probe")
+                    out.append({"placement": place, "k_load_pattern": ["contiguous_1KiB", "mfma_operand_64B_x16", "contiguous_1KiB_into_LDS"][pattern],
                                 "tiles_in_flight": depth, "waves_per_wg": waves, "pages_per_wg": ppw,
                                 "workgroups": rows * ((k + ppw - 1) // ppw), "us": round(us, 2),
                                 "TBps": round(nbytes / us / 1e6, 3)})

@@ -678,7 +678,7 @@ extern "C" int unique_debug_dec_stamps(void** ptr, int* waves, int* slots) {
 // One wave fetches the 4 KiB K tile and the 4 KiB V tile of each of its (physical page, head) entries -- page ids
 // straight from `list`, no page table, no arithmetic but an xor -- with kDepth tiles in flight. kPattern 0: every
 // load instruction covers a contiguous 1 KiB; 1: K in the operand layout of the matrix-core q.k stage (64-byte
-// pieces of 16 rows). Geometry as the decode kernel: rows x ceil(k / pages_per_wg) workgroups of `waves` waves.
+// pieces of 16 rows); 2: contiguous loads that go straight into LDS (second kernel below). Geometry as the decode kernel: rows x ceil(k / pages_per_wg) workgroups of `waves` waves.
 namespace {
 typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));
 template <int kPattern, int kDepth>
@@ -718,6 +718,57 @@ __global__ __launch_bounds__(1024) void gather_probe_kernel(const char* __restri
   }
   if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) sink[threadIdx.x] = acc;  // never true in practice; keeps the loads alive
 }
+
+// The same gather with the tiles sent straight into LDS (global_load_lds_dwordx4, no register between memory and
+// LDS): a ring of kDepth tiles of 8 KiB per wave, each tile waited for with an explicit vmcnt and read back with
+// ds_read_b128. Dynamic LDS: waves * kDepth * 8 KiB.
+template <int kN>
+__device__ __forceinline__ void probe_wait_vmcnt() {  // s_waitcnt vmcnt(kN) alone (expcnt and lgkmcnt fields left at their maximum)
+  __builtin_amdgcn_s_waitcnt((kN & 0xF) | ((kN >> 4) << 14) | 0x0F70);
+}
+template <int kDepth>
+__global__ __launch_bounds__(1024) void gather_probe_lds_kernel(const char* __restrict__ kpool,
+                                                                 const char* __restrict__ vpool,
+                                                                 const int32_t* __restrict__ list, int k, int pages_per_wg,
+                                                                 int waves, int heads, probe_u32x4* __restrict__ sink) {
+  extern __shared__ __attribute__((aligned(16))) char probe_lds[];
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
+  const int begin = split * pages_per_wg, end = min(begin + pages_per_wg, k);
+  const int hkv = row % heads;
+  const int n = min(kWave, (end - begin - wave + waves - 1) / waves);
+  int my_phys = 0;
+  if (lane < n) my_phys = list[(size_t)row * k + begin + wave + lane * waves];
+  char* ring = probe_lds + (size_t)wave * kDepth * 8192;  // wave-uniform
+  probe_u32x4 acc = {0, 0, 0, 0};
+  auto issue = [&](int i, int d) {
+    const int phys = __builtin_amdgcn_readlane(my_phys, max(min(i, n - 1), 0));
+    const size_t base = ((size_t)phys * heads + hkv) * 4096 + lane * 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(kpool + base + j * 1024), (lptr_t)(ring + d * 8192 + j * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(vpool + base + j * 1024), (lptr_t)(ring + d * 8192 + 4096 + j * 1024), 16, 0, 0);
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth; ++d) issue(d, d);
+  for (int i = 0; i < n; i += kDepth) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      probe_wait_vmcnt<(kDepth - 1) * 8>();  // the oldest tile has landed; the younger ones may still be on their way
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc ^= *reinterpret_cast<const probe_u32x4*>(ring + d * 8192 + j * 1024 + lane * 16);
+      asm volatile("" ::"v"(acc.x), "v"(acc.y), "v"(acc.z), "v"(acc.w) : "memory");  // the reads are done before the slot is refilled
+      issue(i + d + kDepth, d);
+    }
+  }
+  probe_wait_vmcnt<0>();
+  if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) sink[threadIdx.x] = acc;
+}
 }  // namespace
 
 // k_pool / v_pool: [num_pages][heads][4096 bytes]; list: int32 [rows][k] physical page ids (all < num_pages, which the
@@ -732,6 +783,18 @@ extern "C" int unique_debug_gather_probe(const void* k_pool, const void* v_pool,
     kernel<<<grid, block, 0, (hipStream_t)stream>>>((const char*)k_pool, (const char*)v_pool, list, k, pages_per_wg,
                                                     waves, heads, (probe_u32x4*)sink);
   };
+  if (pattern == 2) {  // through LDS
+    const size_t lds = (size_t)waves * depth * 8192;
+    if (lds > 160 * 1024 || (depth != 2 && depth != 4)) return (int)hipErrorInvalidValue;
+    auto go_lds = [&](auto kernel) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return (int)e;
+      kernel<<<grid, block, lds, (hipStream_t)stream>>>((const char*)k_pool, (const char*)v_pool, list, k, pages_per_wg,
+                                                        waves, heads, (probe_u32x4*)sink);
+      return (int)hipGetLastError();
+    };
+    return depth == 2 ? go_lds(gather_probe_lds_kernel<2>) : go_lds(gather_probe_lds_kernel<4>);
+  }
   if (pattern == 0 && depth == 2) go(gather_probe_kernel<0, 2>);
   else if (pattern == 0 && depth == 4) go(gather_probe_kernel<0, 4>);
   else if (pattern == 1 && depth == 2) go(gather_probe_kernel<1, 2>);
