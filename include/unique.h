@@ -98,6 +98,12 @@ typedef struct unique_cache_desc {
                                 The S*D elements of one (page, head) are always contiguous. Setting
                                 v_cache = k_cache + S*D, kv_head_stride = 2*S*D and kv_page_stride = H_kv*2*S*D
                                 describes a cache that keeps the K and V tiles of a (page, head) side by side. */
+  int32_t min_seq_len_hint;  /* host LOWER bound on seq_lens[]; 0 = unknown. A performance hint only: a batch whose
+                                sequences are all known to be long lets the page-score launch give each workgroup
+                                more pages (fewer prologues) without the risk of starving compute units on a
+                                ragged batch. Results never depend on it. Must not exceed max_seq_len_hint when
+                                both are given. */
+  int32_t reserved0;         /* 0 */
 } unique_cache_desc;
 
 /* Bytes of device workspace that any of the calls below may need for this descriptor and top_k

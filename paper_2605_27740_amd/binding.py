@@ -30,7 +30,8 @@ class CacheDesc(C.Structure):
                 ("num_phys_pages", C.c_int64), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
                 ("page_stats", C.c_void_p), ("page_table", C.c_void_p), ("seq_lens", C.c_void_p),
                 ("stats_dtype", C.c_int32), ("force_recent_pages", C.c_int32),
-                ("kv_page_stride", C.c_int64), ("kv_head_stride", C.c_int64)]
+                ("kv_page_stride", C.c_int64), ("kv_head_stride", C.c_int64),
+                ("min_seq_len_hint", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class UniqueError(RuntimeError):
@@ -165,7 +166,8 @@ def stats_record_bytes(num_kv_heads: int, head_dim: int, stats_dtype) -> int:
 
 
 def make_desc(*, q_heads: int, k_cache, v_cache, page_stats, page_table, seq_lens,
-              max_seq_len_hint: int = 0, stats_dtype=torch.float32, force_recent_pages: int = 0) -> CacheDesc:
+              max_seq_len_hint: int = 0, stats_dtype=torch.float32, force_recent_pages: int = 0,
+              min_seq_len_hint: int = 0) -> CacheDesc:
     """Fill a ``unique_cache_desc`` from tensors laid out as include/unique.h describes (shape checks only)."""
     P, Hkv, S, D = k_cache.shape
     # the (S, D) tile of one (page, head) must be contiguous; page and head strides are passed through
@@ -181,4 +183,4 @@ def make_desc(*, q_heads: int, k_cache, v_cache, page_stats, page_table, seq_len
                      max_seq_len_hint, P, k_cache.data_ptr(), 0 if v_cache is None else v_cache.data_ptr(),
                      0 if page_stats is None else page_stats.data_ptr(),
                      page_table.data_ptr(), seq_lens.data_ptr(), DTYPE_CODE[stats_dtype], int(force_recent_pages),
-                     k_cache.stride(0), k_cache.stride(1))
+                     k_cache.stride(0), k_cache.stride(1), int(min_seq_len_hint), 0)

@@ -2,6 +2,7 @@
 // kernel dispatch. Nothing here allocates device memory or synchronises.
 #include "../../include/unique.h"
 
+#include <algorithm>
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
@@ -65,6 +66,9 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
   if (d->stats_dtype != UNIQUE_DTYPE_F32 && d->stats_dtype != UNIQUE_DTYPE_BF16)
     return fail(UNIQUE_ERR_INVALID_ARG, "stats_dtype %d is neither fp32 (0) nor bf16 (1)", d->stats_dtype);
   if (d->force_recent_pages < 0) return fail(UNIQUE_ERR_INVALID_ARG, "force_recent_pages must be >= 0");
+  if (d->min_seq_len_hint < 0 || (d->max_seq_len_hint > 0 && d->min_seq_len_hint > d->max_seq_len_hint))
+    return fail(UNIQUE_ERR_INVALID_ARG, "min_seq_len_hint %d must lie in [0, max_seq_len_hint %d]", d->min_seq_len_hint,
+                d->max_seq_len_hint);
   {
     const int64_t tile = (int64_t)d->page_size * d->head_dim;
     const int64_t hs = d->kv_head_stride ? d->kv_head_stride : tile;
@@ -95,6 +99,7 @@ int make_view(const unique_cache_desc* d, unique::CacheView* v, bool need_stats,
     if (hp < hint_pages) hint_pages = (int)hp;
   }
   v->max_pages_hint = hint_pages;
+  v->min_pages_hint = (int)std::min<int64_t>(d->min_seq_len_hint / d->page_size, hint_pages);
   v->stats_bf16 = d->stats_dtype == UNIQUE_DTYPE_BF16;
   v->rec_bytes = unique_page_stats_record_bytes(d);
   v->stream_nt = 0;

@@ -16,6 +16,7 @@ struct CacheView {
   int64_t num_phys;
   int32_t dtype;              // 0 fp32, 1 bf16
   int32_t max_pages_hint;     // host bound on pages of any sequence (<= max_pages)
+  int32_t min_pages_hint;     // host lower bound on full pages of every sequence (0: unknown); sizes tiles only
   int32_t stats_bf16;         // 1: means stored as bf16, 0: fp32
   int64_t rec_bytes;          // bytes per page record of page_stats
   int32_t stream_nt;          // set per launch: read the streamed operand with non-temporal loads

@@ -23,6 +23,9 @@ constexpr int kScoreWaves = 4;
 #ifndef UNIQUE_SCORE_DEPTH
 #define UNIQUE_SCORE_DEPTH 2
 #endif
+#ifndef UNIQUE_SCORE_FULL_TILES
+#define UNIQUE_SCORE_FULL_TILES 512  // full tiles (two per CU) a batch of known-long sequences must supply for the next larger tile
+#endif
 #ifndef UNIQUE_SCORE_FAT_GRID
 #define UNIQUE_SCORE_FAT_GRID 4096  // workgroups above which a launch can afford the next larger tile
 #endif
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   constexpr int kDepth = UNIQUE_SCORE_DEPTH;          // records in flight per wave (deeper rings measured no faster)
 
   const int b = blockIdx.y;
-  const int tile0 = blockIdx.x * tile_pages;  // tile_pages logical pages per workgroup (32, 64 or 128)
+  const int tile0 = blockIdx.x * tile_pages;  // tile_pages logical pages per workgroup (a power of two, 32..256)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;  // wave: scalar
   const int row8 = lane / kRowLanes, cl = lane % kRowLanes;
   // which head and which page of a step this lane's row is; both fixed for the whole kernel
@@ -295,12 +298,18 @@ hipError_t launch_t(const CacheView& cv, const void* q, float lambda, float* sco
                     bool refresh_tail, hipStream_t st) {
   const CacheView& c = cv;
   const bool nt = (int64_t)c.B * c.max_pages_hint * c.rec_bytes > kStreamNtBytes;
-  // Small tiles balance ragged batches and small launches over the 256 CUs; a launch with workgroups to
-  // spare takes larger ones (fewer prologues). A wave keeps the page ids of all its steps in its 64
-  // lanes, which caps the tile at 64 pages when one wave steps through all 32 heads of a page alone.
-  const int max_tile = c.Hkv == 32 ? 64 : 128;
+  // Small tiles balance ragged batches and small launches over the 256 CUs; larger ones save prologues
+  // (fewer, longer streams). A tile is doubled while the batch is known to fill the chip with FULL tiles
+  // of the larger size: either every sequence is long enough by the host's lower bound (at least two
+  // workgroups of equal work per CU), or the launch has workgroups to spare whatever the lengths are.
+  // A wave keeps the page ids of all its steps in its 64 lanes, which caps the tile at 64 pages per wave
+  // slot (4 slots up to 8 KV heads, 2 at 16, 1 when one wave steps through all 32 heads of a page alone).
+  const int wave_slots = c.Hkv <= 8 ? kScoreWaves : kScoreWaves * kRowsPerWave / c.Hkv;
+  const int max_tile = 64 * wave_slots;
   int tile = 32;
-  while (tile < max_tile && (int64_t)c.B * ((c.max_pages_hint + 2 * tile - 1) / (2 * tile)) >= UNIQUE_SCORE_FAT_GRID)
+  while (2 * tile <= max_tile &&
+         ((int64_t)c.B * (c.min_pages_hint / (2 * tile)) >= UNIQUE_SCORE_FULL_TILES ||
+          (int64_t)c.B * ((c.max_pages_hint + 2 * tile - 1) / (2 * tile)) >= UNIQUE_SCORE_FAT_GRID))
     tile *= 2;
   dim3 grid((c.max_pages_hint + tile - 1) / tile, c.B), block(kScoreWaves * kWave);
   const size_t lds = (size_t)c.Hkv * tile * sizeof(float);

@@ -12,7 +12,7 @@ from .workloads import Workload
 class DecodeSession:
     def __init__(self, wl: Workload, top_k: int | None = None, max_seq_len_hint: int | None = None,
                  want_scores: bool = True, lib: binding.Library | None = None, stats_dtype=torch.float32,
-                 force_recent_pages: int = 0):
+                 force_recent_pages: int = 0, min_seq_len_hint: int | None = None):
         assert wl.k_cache.is_cuda, "the workload must live on the GPU"
         self.lib = lib or binding.load()
         self.wl = wl
@@ -30,10 +30,13 @@ class DecodeSession:
         self.page_pad = self.page_stats[:, mean_bytes + 4 * wl.Hkv:]
         if max_seq_len_hint is None:
             max_seq_len_hint = int(wl.seq_lens.max().item()) + int(wl.meta.get("spare_tokens", 0))
+        if min_seq_len_hint is None:  # sequences only grow while a session lives, so today's shortest is a lower bound
+            min_seq_len_hint = min(int(wl.seq_lens.min().item()), max_seq_len_hint)
         self.desc = binding.make_desc(q_heads=wl.H, k_cache=wl.k_cache, v_cache=wl.v_cache,
                                       page_stats=self.page_stats, stats_dtype=stats_dtype,
                                       page_table=wl.page_table, seq_lens=wl.seq_lens,
-                                      max_seq_len_hint=max_seq_len_hint, force_recent_pages=force_recent_pages)
+                                      max_seq_len_hint=max_seq_len_hint, min_seq_len_hint=min_seq_len_hint,
+                                      force_recent_pages=force_recent_pages)
         self.force_recent_pages = int(force_recent_pages)
         self.sel_pages = torch.full((wl.B, wl.Hkv, self.top_k), -7, device=dev, dtype=torch.int32)
         self.sel_count = torch.full((wl.B, wl.Hkv), -7, device=dev, dtype=torch.int32)

@@ -21,7 +21,7 @@ def good_desc(**over):
     # pointers only need to be non-NULL and aligned for validation; nothing dereferences them on the host
     d = dict(dtype=1, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, batch=2,
              max_pages_per_seq=64, max_seq_len_hint=0, num_phys_pages=128, k_cache=0x1000, v_cache=0x2000,
-             page_stats=0x3000, page_table=0x5000, seq_lens=0x6000, stats_dtype=0, force_recent_pages=0, kv_page_stride=0, kv_head_stride=0)
+             page_stats=0x3000, page_table=0x5000, seq_lens=0x6000, stats_dtype=0, force_recent_pages=0, kv_page_stride=0, kv_head_stride=0, min_seq_len_hint=0, reserved0=0)
     d.update(over)
     return CacheDesc(**d)
 
@@ -67,6 +67,8 @@ def test_workspace_bytes(lib):
     (dict(page_table=0), binding.ERR_INVALID_ARG),
     (dict(k_cache=0x1004), binding.ERR_INVALID_ARG),          # misaligned
     (dict(max_seq_len_hint=-1), binding.ERR_INVALID_ARG),
+    (dict(min_seq_len_hint=-1), binding.ERR_INVALID_ARG),
+    (dict(max_seq_len_hint=512, min_seq_len_hint=513), binding.ERR_INVALID_ARG),  # lower bound above the upper one
     (dict(stats_dtype=3), binding.ERR_INVALID_ARG),
     (dict(force_recent_pages=-1), binding.ERR_INVALID_ARG),
     (dict(max_pages_per_seq=2 ** 27, page_size=8, num_q_heads=32, num_kv_heads=32), binding.ERR_UNSUPPORTED),  # item index overflow

@@ -594,6 +594,33 @@ def test_a_list_longer_than_the_sequence_is_walked_to_its_end(gpu_lib, dtype):
             Hn.check_attention_head(sess.out, sess.lse, oc, q, b, h * wl.G + g, np.array(pages, np.int32), wl.dtype)
 
 
+@pytest.mark.parametrize("Hkv,G,stats_dtype", [(2, 4, torch.float32), (8, 1, torch.bfloat16), (8, 2, torch.float32),
+                                              (16, 1, torch.bfloat16), (32, 1, torch.float32)])
+def test_large_score_tiles_on_a_ragged_batch(gpu_lib, Hkv, G, stats_dtype):
+    """min_seq_len_hint only sizes the page-score tiles and results never depend on it: a lower bound that claims
+    every sequence is as long as the longest makes the launch take its largest tile (256 pages up to 8 KV heads,
+    128 at 16, 64 at 32) on a batch that is in fact ragged -- lengths of 1 token, one page, just below, at and just
+    above tile boundaries, whole tiles without a page -- and every row still has to match the oracle."""
+    S, B = 8, 64
+    rng = np.random.default_rng(70 + Hkv)
+    lens = [2048 * S, 1, S, 256 * S - 1, 256 * S, 256 * S + 1, 128 * S + 3, 64 * S, 65 * S - 2, 1027 * S + 5]
+    lens += [int(n) for n in rng.integers(1, 700 * S, size=B - len(lens))]
+    wl = W.build("bigtile", 48, dtype=torch.bfloat16, B=B, H=G * Hkv, Hkv=Hkv, D=64, S=S, seq_lens=lens, top_k=24,
+                 key_mode="shift", plant_mode="one_percent", permute=True).to(DEV)
+    longest = max(lens)
+    sess = DecodeSession(wl, stats_dtype=stats_dtype, max_seq_len_hint=longest, min_seq_len_hint=longest)
+    _, rep = Hn.full_check_batch(wl, sess=sess, dense_heads=[(0, 0), (B - 1, G * Hkv - 1)])
+    say(rep)
+    truthful = DecodeSession(wl, stats_dtype=stats_dtype)          # the real lower bound: 1 token, smallest tiles
+    truthful.update_page_stats()
+    truthful.score_select_topk()
+    torch.cuda.synchronize()
+    assert torch.equal(truthful.sel_pages, sess.sel_pages) and torch.equal(truthful.sel_count, sess.sel_count)
+    for b in range(B):
+        P = wl.num_pages(b)
+        assert torch.equal(truthful.scores[b, :, :P], sess.scores[b, :, :P]), f"scores of sequence {b} depend on the tile"
+
+
 @pytest.mark.parametrize("list_len", [6, 700])
 def test_empty_and_all_invalid_lists_bf16(gpu_lib, list_len):
     """bf16 caches (matrix-core kernel), a list short enough for one chunk per row (the partial kernel writes the
