@@ -33,22 +33,18 @@ constexpr int kRowLanes = 8;                   // lanes per (page, head) row
 constexpr int kRowsPerWave = kWave / kRowLanes;
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
-// kE consecutive query elements as floats (kE = 4 or 8)
+// kE consecutive query elements, loaded as raw 32-bit words, as floats (kE = 4 or 8)
 template <int kE>
-__device__ __forceinline__ void load_q(const float* p, float (&out)[kE]) {
+__device__ __forceinline__ void unpack_q(const uint32_t (&w)[kE], float (&out)[kE], const float*) {
 #pragma unroll
-  for (int i = 0; i < kE; i += 4) {
-    const float4 v = *reinterpret_cast<const float4*>(p + i);
-    out[i] = v.x; out[i + 1] = v.y; out[i + 2] = v.z; out[i + 3] = v.w;
-  }
+  for (int i = 0; i < kE; ++i) out[i] = bits_to_float(w[i]);
 }
 template <int kE>
-__device__ __forceinline__ void load_q(const bf16_t* p, float (&out)[kE]) {
+__device__ __forceinline__ void unpack_q(const uint32_t (&w)[kE / 2], float (&out)[kE], const bf16_t*) {
 #pragma unroll
-  for (int i = 0; i < kE; i += 4) {
-    const uint2 v = *reinterpret_cast<const uint2*>(p + i);
-    out[i] = bits_to_float(v.x << 16); out[i + 1] = bits_to_float(v.x & 0xffff0000u);
-    out[i + 2] = bits_to_float(v.y << 16); out[i + 3] = bits_to_float(v.y & 0xffff0000u);
+  for (int i = 0; i < kE / 2; ++i) {
+    out[2 * i] = bits_to_float(w[i] << 16);
+    out[2 * i + 1] = bits_to_float(w[i] & 0xffff0000u);
   }
 }
 
@@ -175,6 +171,27 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
     if (my_page < min(tile0 + tile_pages, c.max_pages_hint)) my_phys_raw = pt[my_page];
   }
   const int N = c.seq_lens[b];
+  // raw query words of this lane's row: kE elements per chunk, for each of the G heads of the group
+  constexpr int kQWords = kE * (int)sizeof(T) / 4;
+  uint32_t qraw[G][kChunks][kQWords];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int j = 0; j < kChunks; ++j) {
+      const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(q + ((int64_t)b * c.H + hkv * G + g) * D +
+                                                               j * (kE * kRowLanes) + cl * kE);
+      if constexpr (kQWords == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(qsrc);
+        qraw[g][j][0] = v.x; qraw[g][j][1] = v.y;
+      } else {
+#pragma unroll
+        for (int w = 0; w < kQWords; w += 4) {
+          const uint4 v = *reinterpret_cast<const uint4*>(qsrc + w);
+          qraw[g][j][w] = v.x; qraw[g][j][w + 1] = v.y; qraw[g][j][w + 2] = v.z; qraw[g][j][w + 3] = v.w;
+        }
+      }
+    }
+  }
   const int P = min((N + c.S - 1) / c.S, c.max_pages_hint);  // pages beyond the host bound are ignored
   if (tile0 >= P) return;
   const int tile_end = min(tile0 + tile_pages, P);
@@ -190,27 +207,6 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   float qv[kDot2 ? 1 : G][kChunks][kE];
   uint32_t qp[kDot2 ? G : 1][kChunks][kE / 2];
   float off[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float qq = 0.f;
-#pragma unroll
-    for (int j = 0; j < kChunks; ++j) {
-      const T* qsrc = q + ((int64_t)b * c.H + hkv * G + g) * D + j * (kE * kRowLanes) + cl * kE;
-      float qf[kE];
-      load_q<kE>(qsrc, qf);
-#pragma unroll
-      for (int i = 0; i < kE; ++i) qq = fmaf(qf[i], qf[i], qq);
-      if constexpr (kDot2) {
-#pragma unroll
-        for (int i = 0; i < kE / 2; ++i) qp[g][j][i] = reinterpret_cast<const uint32_t*>(qsrc)[i];
-      } else {
-#pragma unroll
-        for (int i = 0; i < kE; ++i) qv[g][j][i] = qf[i];
-      }
-    }
-    qq = group_allreduce<kRowLanes>(qq, OpSum());
-    off[g] = lambda * sqrtf(qq);
-  }
 
   const char* stats = reinterpret_cast<const char*>(c.page_stats);
   const int64_t std_off = (int64_t)c.Hkv * D * (int64_t)sizeof(TS);  // byte offset of the stds inside a record
@@ -272,6 +268,27 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void page_score_kernel(CacheVie
   };
 #pragma unroll
   for (int u = 0; u < kDepth; ++u) issue(u, ring[u], ring_sd[u], ring_phys[u]);
+  // the queries arrived with the page ids; they are unpacked while the first records are on their way
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float qq = 0.f;
+#pragma unroll
+    for (int j = 0; j < kChunks; ++j) {
+      float qf[kE];
+      unpack_q<kE>(qraw[g][j], qf, (const T*)nullptr);
+#pragma unroll
+      for (int i = 0; i < kE; ++i) qq = fmaf(qf[i], qf[i], qq);
+      if constexpr (kDot2) {
+#pragma unroll
+        for (int i = 0; i < kE / 2; ++i) qp[g][j][i] = qraw[g][j][i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < kE; ++i) qv[g][j][i] = qf[i];
+      }
+    }
+    qq = group_allreduce<kRowLanes>(qq, OpSum());
+    off[g] = lambda * sqrtf(qq);
+  }
   for (int st0 = 0; st0 < n_steps; st0 += kDepth) {
 #pragma unroll
     for (int u = 0; u < kDepth; ++u) {
