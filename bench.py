@@ -42,6 +42,8 @@ def parse():
                     help="microbenchmarks at the shapes of the paper's Appendix A / B tables instead of a decode step")
     ap.add_argument("--phase-stamps", action="store_true",
                     help="profiling build: per-wave wall-clock stamps inside the sparse decode kernel of a cold decode step")
+    ap.add_argument("--record-probe", action="store_true",
+                    help="profiling build: the bare stream of page records behind the score kernel (its ceiling) at the 128K batch's shape")
     ap.add_argument("--gather-probe", action="store_true",
                     help="profiling build: the bare K/V gather of the sparse decode (no page table, no arithmetic) at the "
                          "128K batch's shape, for several chunk placements, load patterns and prefetch depths")
@@ -163,8 +165,8 @@ def main():
     if args.paper_shapes:
         paper_shapes(dev)
         return
-    if args.phase_stamps or args.gather_probe:
-        (phase_stamps if args.phase_stamps else gather_probe)(args, dev)
+    if args.phase_stamps or args.gather_probe or args.record_probe:
+        (phase_stamps if args.phase_stamps else gather_probe if args.gather_probe else record_probe)(args, dev)
         return
     stats_dtype = torch.bfloat16 if args.stats_dtype == "bf16" else torch.float32
 
@@ -560,6 +562,44 @@ def gather_probe(args, dev):
                                 "workgroups": rows * ((k + ppw - 1) // ppw), "us": round(us, 2),
                                 "TBps": round(nbytes / us / 1e6, 3)})
     print(json.dumps({"gather_probe": {"bytes": nbytes, "rows": rows, "pages_per_row": k, "results": out}}))
+
+
+def record_probe(args, dev):
+    """The bare memory access of the score kernel at the 128K batch's shape (16 sequences x 8192 pages, page table a
+    random permutation of the pool, or the identity): every page record's mean block (4 KiB of a 4224-byte record =
+    fp32 means, 2 KiB of 2176 = bf16 means) streamed once, kernel durations from the device timestamps, cold (1 GiB
+    rewritten and 1 GiB read before every launch)."""
+    import torch
+    lib, hip, C = _profiling_library()
+    B, P = 16, 8192
+    pool = B * P
+    fn = lib.c.unique_debug_record_probe
+    fn.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    sink = torch.zeros((4096,), dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu"); g.manual_seed(7)
+    tables = {"permuted": torch.randperm(pool, generator=g).to(torch.int32).view(B, P).to(dev),
+              "identity": torch.arange(pool, dtype=torch.int32).view(B, P).to(dev)}
+    flush_w = torch.zeros((1 << 30,), dtype=torch.uint8, device=dev)
+    flush_r = torch.zeros((1 << 28,), dtype=torch.int32, device=dev)
+    out = []
+    for rec, loads in ((4224, 4), (2176, 2)):
+        stats = torch.ones((pool, rec), dtype=torch.uint8, device=dev)
+        for place, table in tables.items():
+            for tile in (32, 64, 128, 256):
+                for depth in (2, 4, 8):
+                    def call(i):
+                        flush_w.add_(1); flush_r.sum()
+                        rc = fn(stats.data_ptr(), rec, loads, table.data_ptr(), P, P, B, tile, depth, sink.data_ptr(), stream)
+                        assert rc == 0, rc
+                    call(0); torch.cuda.synchronize()
+                    us = _device_kernel_us(torch, call, 10, "record_probe")
+                    nbytes = pool * loads * 1024
+                    out.append({"record_bytes": rec, "bytes_read_per_record": loads * 1024, "page_table": place, "pages_per_wg": tile,
+                                "workgroups": B * ((P + tile - 1) // tile), "records_in_flight_per_wave": depth,
+                                "us": round(us, 2), "TBps": round(nbytes / us / 1e6, 3), "frac_of_8TBps": round(nbytes / us / 8e6, 3)})
+        del stats
+    print(json.dumps({"record_probe": {"batch": B, "pages_per_sequence": P, "results": out}}))
 
 
 def paper_shapes(dev):

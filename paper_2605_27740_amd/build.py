@@ -52,19 +52,25 @@ def build_library(force: bool = False, extra_flags: list[str] | None = None, job
 PROF_LIB_PATH = os.path.join(HERE, "libunique_gfx950_prof.so")
 
 
+PROF_ONLY_SOURCES = ["probes.hip"]  # compiled into the profiling build only
+
+
 def build_profiling_library(force: bool = False) -> str:
     """The profiling build: the product objects with decode.hip recompiled under -DUNIQUE_DEC_STAMPS (per-wave
-    wall-clock stamps in the sparse decode kernel, the bare gather probe). Used by bench.py --phase-stamps and
-    --gather-probe only."""
+    wall-clock stamps in the sparse decode kernel, the bare gather probe) plus probes.hip (the bare record stream of
+    the score kernel). Used by bench.py --phase-stamps, --gather-probe and --record-probe only."""
     build_library()
-    if not force and os.path.exists(PROF_LIB_PATH) and os.path.getmtime(PROF_LIB_PATH) >= _deps_mtime():
+    prof_srcs = [os.path.join(CSRC, s) for s in PROF_ONLY_SOURCES]
+    if (not force and os.path.exists(PROF_LIB_PATH)
+            and os.path.getmtime(PROF_LIB_PATH) >= max(_deps_mtime(), *(os.path.getmtime(p) for p in prof_srcs))):
         return PROF_LIB_PATH
-    obj = os.path.join(OBJ_DIR, "decode_prof.o")
-    cmd = [HIPCC, *FLAGS, "-DUNIQUE_DEC_STAMPS", "-c", os.path.join(CSRC, "decode.hip"), "-o", obj]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed for the profiling build of decode.hip:\n{r.stderr}")
-    objs = [obj] + [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES if s != "decode.hip"]
+    jobs = [(["-DUNIQUE_DEC_STAMPS"], os.path.join(CSRC, "decode.hip"), os.path.join(OBJ_DIR, "decode_prof.o"))]
+    jobs += [([], p, os.path.join(OBJ_DIR, os.path.basename(p).replace(".hip", "_prof.o"))) for p in prof_srcs]
+    for defs, src, obj in jobs:
+        r = subprocess.run([HIPCC, *FLAGS, *defs, "-c", src, "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for the profiling build of {os.path.basename(src)}:\n{r.stderr}")
+    objs = [j[2] for j in jobs] + [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES if s != "decode.hip"]
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROF_LIB_PATH, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
