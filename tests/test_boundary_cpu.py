@@ -39,6 +39,19 @@ def test_exports_match_header(lib):
     assert lib.c.unique_page_stats_record_bytes(None) == 0 and lib.page_stats_record_bytes(good_desc(stats_dtype=5)) == 0
 
 
+def test_debug_exports_live_in_the_profiling_build_only(lib):
+    """The product library exports nothing but what include/unique.h declares; the stamps and the two ceiling probes
+    exist only in the profiling build that bench.py's analysis modes load."""
+    import subprocess
+    from paper_2605_27740_amd import build
+    def exported(path):
+        out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+        return {ln.split()[-1] for ln in out.splitlines() if ln.split()[-1].startswith("unique_")}
+    assert exported(build.LIB_PATH) == set(binding.EXPORTS)
+    debug = {"unique_debug_dec_stamps", "unique_debug_gather_probe", "unique_debug_record_probe"}
+    assert exported(build.build_profiling_library()) == set(binding.EXPORTS) | debug
+
+
 def test_workspace_bytes(lib):
     n = lib.workspace_bytes(good_desc(), 16)
     assert n > 0 and n % 256 == 0
