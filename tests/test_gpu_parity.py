@@ -365,7 +365,9 @@ def test_strided_cache_with_k_and_v_side_by_side(gpu_lib, maker):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("seed", range(24))
+# the seeds beyond 23 are draws whose bf16 statistics hold a page of cancelling keys (a mean far below the fp32
+# accumulation bound), found by running the sweep over several hundred more seeds
+@pytest.mark.parametrize("seed", list(range(24)) + [39, 119, 149, 248, 278])
 def test_random_shape_sweep(gpu_lib, seed):
     """Seeded random draws over every supported (dtype, D, S, G, Hkv), ragged lengths, k, statistics format and
     cache layout; all rows checked against the oracle through the one-call step and the separate calls."""
@@ -783,9 +785,9 @@ def test_config5_full_size_all_rows(gpu_lib, top_k, stats_dtype):
 
 
 def test_bf16_mean_rounding_summary(gpu_lib):
-    """Totals over the bf16-statistics tests of this session: how many stored means were the neighbour of the oracle's
-    rounding (allowed only within the fp32 accumulation bound of a rounding boundary) and the worst
-    |mean - boundary| / bound among them."""
+    """Totals over the bf16-statistics tests of this session: how many stored means differed from the oracle's rounding
+    (allowed only where they are the rounding of a number within the fp32 accumulation bound of the float64 mean) and
+    the largest fraction of that bound any of them needed."""
     say(f"bf16 means checked bit for bit: {Hn.BF16_TIES}")
     assert Hn.BF16_TIES["worst_ratio"] <= 1.0
 

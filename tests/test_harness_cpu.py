@@ -110,3 +110,18 @@ def test_bf16_mean_rule_accepts_the_oracle_rounding_and_justified_neighbours_onl
     mean2[4, 7] = 0.5 * (lo + hi) + 1e-5
     with pytest.raises(AssertionError):
         Hn.check_bf16_means(other, mean2, akm)
+    # keys that cancel: a float64 mean of 2e-9 under a bound of 8.6e-7. An fp32 sum of the same keys may land anywhere
+    # within the bound, also on the other side of zero, many bf16 values away from the oracle's rounding: accepted;
+    # a stored value beyond the bound is not
+    mean3 = mean.copy()
+    mean3[0, 0] = 2e-9
+    want3 = oracle.round_bf16(mean3)
+    for v, fine in ((-3e-7, True), (5e-7, True), (0.0, True), (-2e-6, False), (3e-6, False)):
+        stored = want3.copy()
+        stored[0, 0] = oracle.round_bf16(np.array([v]))[0]
+        if fine:
+            used, (n, worst) = Hn.check_bf16_means(stored, mean3, akm)
+            assert n == 1 and 0 < worst <= 1.0 and used[0, 0] == oracle.bf16_to_double(stored[0:1, 0])[0]
+        else:
+            with pytest.raises(AssertionError):
+                Hn.check_bf16_means(stored, mean3, akm)
