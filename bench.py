@@ -8,7 +8,11 @@ unique_dense_paged_decode (Eq. 4) is timed beside it as the in-library compariso
 CPU oracle is timed on a bounded sample of the same workload as a reported baseline.
 
 Prints ONE JSON line (see the keys at the bottom). Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
-[--workload c2|c3|c4|c5] [--top-k K] [--no-cpu-baseline] [--copy-calibration BYTES]
+[--workload c2|c3|c4|c5] [--stats-dtype fp32|bf16] [--top-k K] [--no-cpu-baseline] [--no-dense] [--copy-calibration BYTES]
+Analysis modes, each printing one JSON line of its own: --paper-shapes (the shapes of the paper's Appendix A / B tables
+and Fig. 2), and, on the profiling build of the library, --phase-stamps (where the sparse decode kernel's time goes),
+--gather-probe (the bare K/V gather behind it) and --record-probe (the bare stream of page records behind the score
+kernel).
 """
 import argparse
 import json
