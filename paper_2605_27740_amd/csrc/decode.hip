@@ -416,17 +416,6 @@ __global__ __launch_bounds__(kDecWaves* kWave) void paged_decode_partial_mfma_ke
       }
     };
     auto consume = [&](const Raw16(&kr)[kSteps], const Raw16(&vr)[kVLoads], bool kvalid_cur) {
-#ifdef UNIQUE_DEC_EXPERIMENT_NO_COMPUTE   // timing experiment only (wrong results): the loads with a trivial consumer
-      {
-        uint32_t x = 0;
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) x ^= kr[s].v.x ^ kr[s].v.y ^ kr[s].v.z ^ kr[s].v.w;
-#pragma unroll
-        for (int j = 0; j < kVLoads; ++j) x ^= vr[j].v.x ^ vr[j].v.y ^ vr[j].v.z ^ vr[j].v.w;
-        acc[0][0] += __uint_as_float(x & 0x3fffffffu) * (kvalid_cur ? 1.f : 0.f);
-        return;
-      }
-#endif
       f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < kSteps; ++s)
